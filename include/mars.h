@@ -1,0 +1,188 @@
+/*
+ * mars.h -- C ABI of the MARS verification pass for AMD MI355X (gfx950).
+ *
+ * MARS (margin-aware speculative verification) changes only the accept/reject
+ * rule of speculative decoding (paper Sec. 2.3 last paragraph, Sec. 3.4,
+ * Algorithm 1).  This library is the verification pass over the target model's
+ * logits for every node of a drafted chain or token tree:
+ *
+ *   - per-row top-1 / top-2 over the vocabulary (Sec. 3.3: v(1), v(2),
+ *     z(1) >= z(2)) and, when sampling, max / sum-exp of the softmax (Eq. 3);
+ *   - the logit ratio r = z(2)/z(1) (Eq. 4, "ratio_def") and the margin test
+ *     r > theta (Sec. 3.4 "Adaptive Relaxation");
+ *   - per-node acceptance: exact match / relaxed runner-up / reject (Alg. 1)
+ *     in greedy mode, the rejection-sampling test min(1, P_t/P_s) (Eq. 1)
+ *     plus the relaxed runner-up in sampling mode;
+ *   - residual-distribution resampling after a rejection (Sec. 2.3);
+ *   - longest accepted path over the chain or tree (Sec. 2.3 tree paragraph)
+ *     and the correction / bonus token (Alg. 1 "Correction"; Table 1 caption:
+ *     tau <= K+1).
+ *
+ * Conventions
+ *   B requests, N nodes per request INCLUDING the root (node 0 = the last
+ *   committed token), V vocabulary entries.  logits[b,i,:] is the target's
+ *   next-token row after node i; node i >= 1 is verified against the row of
+ *   parent(i); the correction / bonus token comes from the row of the last
+ *   accepted node.  A chain of K drafts is N = K+1 with parent(i) = i-1.
+ *
+ *   Ties are ordered (value descending, index ascending): id1 is the lowest
+ *   index holding the maximum, id2 the lowest index, other than id1, holding
+ *   the maximum of the rest.
+ *
+ *   Relaxation needs z(1) > 0 (the paper's positive-domain assumption,
+ *   Sec. 3.3) and the strict inequality fl32(z(2)/z(1)) > theta[b], evaluated
+ *   with one correctly rounded fp32 division.
+ *
+ * All pointers are DEVICE pointers unless stated.  The library never frees or
+ * keeps caller memory.  Calls only enqueue work on the given HIP stream;
+ * outputs are valid once that stream has been synchronised.  No exceptions
+ * and no C++ types cross this boundary.
+ */
+#ifndef MARS_H_
+#define MARS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element type of logits / draft_probs. */
+enum { MARS_F32 = 0, MARS_BF16 = 1 };
+
+/* Return codes (host-detectable errors enqueue nothing). */
+enum {
+  MARS_OK            = 0,
+  MARS_ERR_ARG       = -1, /* null required pointer, B/N/V out of range, T < 0 or NaN */
+  MARS_ERR_DTYPE     = -2, /* unknown element type */
+  MARS_ERR_WORKSPACE = -3, /* workspace missing, misaligned or too small */
+  MARS_ERR_HIP       = -4  /* a HIP call (launch, attribute query) failed */
+};
+
+/* Per-request status written by the device (data-dependent problems). */
+enum {
+  MARS_REQ_OK        = 0,
+  MARS_REQ_BAD_TREE  = 1, /* parent[0] != -1, or parent[i] not in [0, i) for i >= 1 */
+  MARS_REQ_BAD_TOKEN = 2  /* draft token of a node i >= 1 outside [0, V) */
+};
+
+/* decision[b,i] codes (Sec. 3.4 bullets; code 3 is Eq. 1's stochastic accept). */
+enum {
+  MARS_DEC_NONE    = 0, /* not on the selected path */
+  MARS_DEC_EXACT   = 1, /* draft token == v(1) (greedy mode) */
+  MARS_DEC_RELAXED = 2, /* draft token == v(2) and r > theta */
+  MARS_DEC_SAMPLED = 3  /* accepted by u < min(1, f(x)/q(x)) (sampling mode) */
+};
+
+/* Largest N (nodes per request, root included) and smallest V accepted. */
+#define MARS_MAX_NODES 1024
+#define MARS_MIN_VOCAB 2
+
+/* Per-row statistics table, one entry per (b, i) row, 24 bytes.
+ * z1/z2 are the logit values widened exactly to fp32.  sum_exp is
+ * S = sum_v exp((z_v - z1)/T) (Eq. 3 with the max subtracted); 0 in greedy mode. */
+typedef struct mars_row_stat {
+  float   z1;
+  int32_t id1;
+  float   z2;
+  int32_t id2;
+  float   sum_exp;
+  int32_t relax_ok; /* 1 iff z1 > 0 and fl32(z2/z1) > theta[b] */
+} mars_row_stat;
+
+/* Optional per-request diagnostics of the sampling-mode walk (floats the
+ * parity tests compare against the oracle). */
+typedef struct mars_req_diag {
+  float   bonus_prob;      /* f(bonus_token) / sum_v f(v) for the final distribution f the token is drawn from */
+  float   last_residual_norm; /* Z = sum_v max(0, f - q) of the last rejection (0 if none) */
+  int32_t residual_passes; /* number of rejections, i.e. residual renormalisations performed */
+  int32_t last_node;       /* node whose row produced the bonus token */
+} mars_req_diag;
+
+/* Library version: major*10000 + minor*100 + patch. */
+int mars_version(void);
+
+/* Static string for a return code (host memory, never freed). */
+const char* mars_status_string(int status);
+
+/*
+ * Bytes of device workspace mars_verify / mars_row_stats need for these sizes
+ * (0 if an argument is out of range).  The workspace must be 256-byte aligned.
+ * Its contents are scratch: undefined before and after a call.
+ */
+size_t mars_workspace_bytes(int B, int N, int V);
+
+/*
+ * Row reduction only (Sec. 3.3 top-2, Eq. 3 sum-exp, Eq. 4 ratio test):
+ * fills stats[B*N].  temperature == 0 skips the sum-exp (sum_exp = 0).
+ *
+ *   logits       device, [B,N,V] row-major, element type logits_dtype, rows contiguous
+ *                (row stride V elements).  No NaN / +inf; -inf = masked token.
+ *   theta        device, [B] fp32 per-request threshold.
+ *   stats        device out, [B*N].
+ *   workspace    device, >= mars_workspace_bytes(B,N,V), 256-byte aligned.
+ *   hip_stream   hipStream_t (NULL = default stream).
+ * Returns MARS_OK or a negative code; on error nothing is enqueued.
+ */
+int mars_row_stats(const void* logits, int logits_dtype, const float* theta,
+                   float temperature, int B, int N, int V, mars_row_stat* stats,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The whole verification pass.
+ *
+ *   logits        device, [B,N,V] as above.
+ *   draft_tokens  device, [B,N] int32; [b,0] is the root token (never read).
+ *   tree_parent   device, [B,N] int32; [b,0] = -1; 0 <= parent[b,i] < i for i >= 1.
+ *   draft_probs   device, [B,N,V] (element type draft_dtype): the draft model's
+ *                 distribution AFTER node i, i.e. the one the children of i were
+ *                 drawn from (Eq. 1's P_Ms).  Non-negative; used as given.
+ *                 NULL = deterministic draft: q is one-hot at each child's token.
+ *                 Ignored in greedy mode.
+ *   theta         device, [B] fp32 thresholds (Sec. 3.4; the paper uses 0.9).
+ *   temperature   host scalar.  0 selects greedy verification (Alg. 1 on a tree,
+ *                 correction = v(1)).  > 0 selects sampling verification with
+ *                 p = softmax(z / T): relaxed runner-up accept, else Eq. 1,
+ *                 residual resampling on rejection.
+ *   uniforms      device, [B,N+1] fp32 in [0,1): [b,i] tests node i (i >= 1),
+ *                 [b,N] draws the correction / bonus token.  May be NULL when
+ *                 temperature == 0.
+ *   accept_mask   device out, [B,N] uint8: 1 iff node on the selected path (root always 1).
+ *   accept_len    device out, [B] int32: accepted draft tokens (root and bonus
+ *                 excluded); tau = accept_len + 1.
+ *   path_idx      device out, [B,N] int32: node at depth 1..accept_len, then -1.
+ *   bonus_token   device out, [B] int32.
+ *   decision      device out, optional (NULL ok), [B,N] uint8 MARS_DEC_* codes.
+ *   request_status device out, optional (NULL ok), [B] int32 MARS_REQ_* codes.  A
+ *                 request with a non-zero status gets accept_len = 0, an empty path
+ *                 and bonus_token = v(1) of its root row.
+ *   stats         device out, optional (NULL ok), [B*N] row statistics.
+ *   diag          device out, optional (NULL ok), [B]; zero-filled in greedy mode.
+ *   workspace     device, >= mars_workspace_bytes(B,N,V), 256-byte aligned.
+ *   hip_stream    hipStream_t (NULL = default stream).
+ *
+ * Sampling-mode walk: starting at the root, the children of the current node
+ * are tried in increasing node index against the current distribution f
+ * (initially the node's softmax); the first accepted child becomes the current
+ * node with a fresh f; every rejected child replaces f by norm(max(0, f - q)).
+ * When no child is accepted the token is drawn from f by inverse CDF in index
+ * order with uniforms[b,N].
+ *
+ * Returns MARS_OK or a negative code; on error nothing is enqueued.
+ * Calls that share a workspace must not overlap.
+ */
+int mars_verify(const void* logits, int logits_dtype,
+                const int32_t* draft_tokens, const int32_t* tree_parent,
+                const void* draft_probs, int draft_dtype,
+                const float* theta, float temperature, const float* uniforms,
+                int B, int N, int V,
+                uint8_t* accept_mask, int32_t* accept_len, int32_t* path_idx,
+                int32_t* bonus_token, uint8_t* decision, int32_t* request_status,
+                mars_row_stat* stats, mars_req_diag* diag,
+                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MARS_H_ */
