@@ -1,0 +1,161 @@
+"""ctypes binding of libmars.so -- argument marshalling only.
+
+The functions mirror include/mars.h name for name.  Tensors are torch CUDA tensors
+(ROCm); bf16 logits may be given as ``torch.bfloat16`` or as ``torch.uint16``/``int16``
+bit patterns.  Every call enqueues on the current torch stream and returns without
+synchronising.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmars.so")
+
+MARS_F32, MARS_BF16 = 0, 1
+MARS_OK = 0
+MARS_MAX_NODES = 1024
+
+_lib = None
+
+
+class MarsError(RuntimeError):
+    pass
+
+
+def lib():
+    """Load libmars.so (built by ``paper_2601_15498_amd.build``); fails loudly when missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise MarsError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_15498_amd.build` "
+                            "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        L.mars_version.restype = ctypes.c_int
+        L.mars_status_string.restype = ctypes.c_char_p
+        L.mars_status_string.argtypes = [ctypes.c_int]
+        L.mars_workspace_bytes.restype = ctypes.c_size_t
+        L.mars_workspace_bytes.argtypes = [ctypes.c_int] * 3
+        L.mars_row_stats.restype = ctypes.c_int
+        L.mars_row_stats.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_float,
+                                     ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                     ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.mars_verify.restype = ctypes.c_int
+        L.mars_verify.argtypes = ([ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                   ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_float,
+                                   ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+                                  + [ctypes.c_void_p] * 8 + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p])
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != MARS_OK:
+        raise MarsError(f"mars call failed: {rc} ({lib().mars_status_string(rc).decode()})")
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return MARS_F32
+    if t.dtype in (torch.bfloat16, torch.uint16, torch.int16):
+        return MARS_BF16
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+# struct mars_row_stat {float z1; int32 id1; float z2; int32 id2; float sum_exp; int32 relax_ok;}  (24 bytes)
+ROW_STAT_WORDS = 6
+# struct mars_req_diag {float bonus_prob; float last_residual_norm; int32 residual_passes; int32 last_node;}
+REQ_DIAG_WORDS = 4
+
+
+def mars_version() -> int:
+    return int(lib().mars_version())
+
+
+def mars_workspace_bytes(B: int, N: int, V: int) -> int:
+    return int(lib().mars_workspace_bytes(B, N, V))
+
+
+def alloc_workspace(B: int, N: int, V: int, device="cuda") -> torch.Tensor:
+    n = mars_workspace_bytes(B, N, V)
+    if n == 0:
+        raise MarsError(f"sizes out of range: B={B} N={N} V={V}")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def mars_row_stats(logits: torch.Tensor, theta: torch.Tensor, temperature: float, stats: torch.Tensor = None,
+                   workspace: torch.Tensor = None) -> torch.Tensor:
+    """Row statistics table as an int32 tensor [B*N, 6] (see ``unpack_stats``)."""
+    B, N, V = logits.shape
+    assert logits.is_contiguous() and theta.dtype == torch.float32 and theta.numel() == B
+    if stats is None:
+        stats = torch.empty((B * N, ROW_STAT_WORDS), dtype=torch.int32, device=logits.device)
+    if workspace is None:
+        workspace = alloc_workspace(B, N, V, logits.device)
+    _check(lib().mars_row_stats(_ptr(logits), _dtype_code(logits), _ptr(theta), float(temperature), B, N, V,
+                                _ptr(stats), _ptr(workspace), workspace.numel(), _stream()))
+    return stats
+
+
+def unpack_stats(stats: torch.Tensor) -> dict:
+    s = stats.view(-1, ROW_STAT_WORDS)
+    return {"z1": s[:, 0].view(torch.float32), "id1": s[:, 1], "z2": s[:, 2].view(torch.float32),
+            "id2": s[:, 3], "sum_exp": s[:, 4].view(torch.float32), "relax_ok": s[:, 5]}
+
+
+def unpack_diag(diag: torch.Tensor) -> dict:
+    d = diag.view(-1, REQ_DIAG_WORDS)
+    return {"bonus_prob": d[:, 0].view(torch.float32), "last_residual_norm": d[:, 1].view(torch.float32),
+            "residual_passes": d[:, 2], "last_node": d[:, 3]}
+
+
+class VerifyOutputs:
+    """Device tensors written by ``mars_verify``."""
+
+    def __init__(self, B: int, N: int, device, want_stats: bool = True, want_diag: bool = True):
+        self.accept_mask = torch.empty((B, N), dtype=torch.uint8, device=device)
+        self.accept_len = torch.empty((B,), dtype=torch.int32, device=device)
+        self.path_idx = torch.empty((B, N), dtype=torch.int32, device=device)
+        self.bonus_token = torch.empty((B,), dtype=torch.int32, device=device)
+        self.decision = torch.empty((B, N), dtype=torch.uint8, device=device)
+        self.request_status = torch.empty((B,), dtype=torch.int32, device=device)
+        self.stats = torch.empty((B * N, ROW_STAT_WORDS), dtype=torch.int32, device=device) if want_stats else None
+        self.diag = torch.empty((B, REQ_DIAG_WORDS), dtype=torch.int32, device=device) if want_diag else None
+
+
+def mars_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: torch.Tensor,
+                theta: torch.Tensor, temperature: float, uniforms: torch.Tensor = None,
+                draft_probs: torch.Tensor = None, out: VerifyOutputs = None,
+                workspace: torch.Tensor = None) -> VerifyOutputs:
+    """The whole verification pass; see include/mars.h for argument meaning and layout."""
+    B, N, V = logits.shape
+    dev = logits.device
+    assert logits.is_contiguous()
+    assert draft_tokens.dtype == torch.int32 and draft_tokens.shape == (B, N) and draft_tokens.is_contiguous()
+    assert tree_parent.dtype == torch.int32 and tree_parent.shape == (B, N) and tree_parent.is_contiguous()
+    assert theta.dtype == torch.float32 and theta.numel() == B
+    if uniforms is not None:
+        assert uniforms.dtype == torch.float32 and uniforms.shape == (B, N + 1) and uniforms.is_contiguous()
+    dcode = 0
+    if draft_probs is not None:
+        assert draft_probs.shape == (B, N, V) and draft_probs.is_contiguous()
+        dcode = _dtype_code(draft_probs)
+    if out is None:
+        out = VerifyOutputs(B, N, dev)
+    if workspace is None:
+        workspace = alloc_workspace(B, N, V, dev)
+    _check(lib().mars_verify(_ptr(logits), _dtype_code(logits), _ptr(draft_tokens), _ptr(tree_parent),
+                             _ptr(draft_probs), dcode, _ptr(theta), float(temperature), _ptr(uniforms),
+                             B, N, V, _ptr(out.accept_mask), _ptr(out.accept_len), _ptr(out.path_idx),
+                             _ptr(out.bonus_token), _ptr(out.decision), _ptr(out.request_status),
+                             _ptr(out.stats), _ptr(out.diag), _ptr(workspace), workspace.numel(), _stream()))
+    return out

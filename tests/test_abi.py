@@ -1,0 +1,95 @@
+"""The C-ABI library loads, exports every function include/mars.h declares, and rejects bad
+arguments on the host before anything is enqueued.  No GPU needed: no call here reaches a kernel."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mars.h")
+LIB = os.path.join(ROOT, "paper_2601_15498_amd", "libmars.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2601_15498_amd import build
+        build.build()
+    from paper_2601_15498_amd import binding
+    return binding.lib()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mars_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    assert declared_functions() == ["mars_row_stats", "mars_status_string", "mars_verify", "mars_version",
+                                    "mars_workspace_bytes"]
+
+
+def test_every_declared_symbol_is_exported(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_struct_sizes_match_the_binding():
+    from paper_2601_15498_amd import binding
+    text = open(HEADER).read()
+    row = re.search(r"typedef struct mars_row_stat \{(.*?)\}", text, re.S).group(1)
+    diag = re.search(r"typedef struct mars_req_diag \{(.*?)\}", text, re.S).group(1)
+    assert len(re.findall(r"\b(float|int32_t)\b", re.sub(r"/\*.*?\*/", "", row, flags=re.S))) == binding.ROW_STAT_WORDS
+    assert len(re.findall(r"\b(float|int32_t)\b", re.sub(r"/\*.*?\*/", "", diag, flags=re.S))) == binding.REQ_DIAG_WORDS
+
+
+def test_version_and_status_strings(lib):
+    assert lib.mars_version() >= 100
+    assert lib.mars_status_string(0) == b"ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert len(lib.mars_status_string(code)) > 0
+
+
+def test_workspace_bytes(lib):
+    assert lib.mars_workspace_bytes(16, 60, 151936) > 0
+    assert lib.mars_workspace_bytes(16, 60, 151936) % 256 == 0
+    assert lib.mars_workspace_bytes(1, 1, 2) > 0
+    for B, N, V in ((0, 60, 100), (1, 0, 100), (1, 1025, 100), (1, 5, 1), (-3, 5, 100)):
+        assert lib.mars_workspace_bytes(B, N, V) == 0
+
+
+def test_host_side_argument_errors_enqueue_nothing(lib):
+    p = ctypes.c_void_p(0x1000)  # never dereferenced: every case below fails validation first
+    null = ctypes.c_void_p(0)
+    ok = dict(logits=p, ldt=0, tok=p, par=p, dq=null, ddt=0, theta=p, T=0.0, u=null, B=2, N=4, V=100,
+              mask=p, alen=p, path=p, bonus=p, dec=null, st=null, stats=null, diag=null, ws=p, wsb=1 << 20, stream=null)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return lib.mars_verify(a["logits"], a["ldt"], a["tok"], a["par"], a["dq"], a["ddt"], a["theta"],
+                               ctypes.c_float(a["T"]), a["u"], a["B"], a["N"], a["V"], a["mask"], a["alen"],
+                               a["path"], a["bonus"], a["dec"], a["st"], a["stats"], a["diag"], a["ws"],
+                               ctypes.c_size_t(a["wsb"]), a["stream"])
+
+    assert call(logits=null) == -1 and call(tok=null) == -1 and call(par=null) == -1 and call(theta=null) == -1
+    assert call(mask=null) == -1 and call(alen=null) == -1 and call(path=null) == -1 and call(bonus=null) == -1
+    assert call(B=0) == -1 and call(N=0) == -1 and call(N=1025) == -1 and call(V=1) == -1
+    assert call(T=-0.5) == -1 and call(T=float("nan")) == -1 and call(T=float("inf")) == -1
+    assert call(T=1.0, u=null) == -1            # sampling needs uniforms
+    assert call(ldt=7) == -2
+    assert call(T=1.0, u=p, dq=p, ddt=5) == -2
+    assert call(ws=null) == -3 and call(wsb=16) == -3 and call(ws=ctypes.c_void_p(0x1010)) == -3
+    rs = lib.mars_row_stats
+    assert rs(null, 0, p, ctypes.c_float(0.0), 1, 1, 10, p, p, ctypes.c_size_t(1 << 20), null) == -1
+    assert rs(p, 3, p, ctypes.c_float(0.0), 1, 1, 10, p, p, ctypes.c_size_t(1 << 20), null) == -2
+    assert rs(p, 0, p, ctypes.c_float(0.0), 1, 1, 10, p, p, ctypes.c_size_t(8), null) == -3
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    from paper_2601_15498_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(binding.MarsError):
+        binding.lib()

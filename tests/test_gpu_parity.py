@@ -1,0 +1,249 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Every test here needs a real MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from mars_inputs import Workload, f32_to_bf16_bits, make_config, make_workload, random_tree, chain_parents
+from tests.gpu_util import compare, run_gpu, say, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu_and_lib():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2601_15498_amd import binding
+    binding.lib()  # fails loudly when libmars.so is missing: there is no fallback
+    say(f"[gpu] {torch.cuda.get_device_name(0)} libmars {binding.mars_version()}")
+
+
+def custom(name, logits, tok, par, theta, T, u=None, q=None):
+    logits = np.ascontiguousarray(logits)
+    B, N, V = logits.shape
+    th = np.full(B, theta, np.float32) if np.ndim(theta) == 0 else np.asarray(theta, np.float32)
+    return Workload(name=name, B=B, N=N, V=V, dtype="bf16" if logits.dtype == np.uint16 else "f32",
+                    temperature=float(T), theta=th, logits=logits,
+                    draft_tokens=np.ascontiguousarray(tok, dtype=np.int32),
+                    tree_parent=np.ascontiguousarray(par, dtype=np.int32),
+                    uniforms=None if u is None else np.ascontiguousarray(u, dtype=np.float32),
+                    draft_probs=None if q is None else np.ascontiguousarray(q))
+
+
+# ----------------------------------------------------------------------------- the paper-shaped configurations
+def test_cfg0_greedy_chain_f32():
+    compare(make_config(0))
+
+
+@pytest.mark.parametrize("T", [0.0, 1.0])
+def test_cfg1_tree60_bf16(T):
+    compare(make_config(1, temperature=T), label=f"cfg1_T{T}")
+
+
+def test_cfg2_reduced_dense_q():
+    # same recipe, B=3: spans many tiles of the row kernel and several residual passes
+    compare(make_config(2, B=3), label="cfg2_B3")
+
+
+def test_cfg2_full_dense_q():
+    compare(make_config(2))
+
+
+def test_cfg3_full_per_request_theta():
+    s = compare(make_config(3))
+    assert s["relaxed"] > 0
+
+
+def test_cfg4_reduced():
+    compare(make_config(4, B=12), label="cfg4_B12")
+
+
+def test_cfg4_full_4gb():
+    compare(make_config(4))
+
+
+# ----------------------------------------------------------------------------- worked examples through the library
+def test_worked_examples_on_gpu():
+    z = np.array([[[1, 10, 9.5, 2, -3], [8, 1, 0, 5, 2], [2, 3, 20, 14, 1], [0, 0, 0, 7, 1]]], np.float32)
+    par = [[-1, 0, 1, 2]]
+    for theta in (0.9, 1.5):
+        compare(custom(f"W1_theta{theta}", z, [[0, 2, 0, 3]], par, theta, 0.0))
+    compare(custom("W1_all_accepted", z, [[0, 2, 0, 2]], par, 0.9, 0.0))
+    z4 = np.log(np.array([[[6, 3, 1], [1, 1, 1], [1, 3, 1]]], np.float64)).astype(np.float32)
+    compare(custom("W4", z4, [[0, 1, 2]], [[-1, 0, 0]], 0.9, 1.0, u=[[0, 0.5, 0.1, 0.75]]), screened=False)
+    compare(custom("W4b", z4, [[0, 1, 2]], [[-1, 0, 0]], 0.9, 1.0, u=[[0, 0.5, 0.2, 0.3]]), screened=False)
+    z5 = np.log(np.array([[[0.4, 0.35, 0.25], [1, 1, 1], [1, 1, 1]]], np.float64)).astype(np.float32)
+    q5 = np.array([[[0.1, 0.3, 0.6], [1 / 3] * 3, [1 / 3] * 3]], np.float32)
+    compare(custom("W5_two_dense_siblings", z5, [[0, 2, 1]], [[-1, 0, 0]], 2.0, 1.0, u=[[0, 0.5, 0.9, 0.3]], q=q5),
+            screened=False)
+    z6 = np.array([[[10, 9.5, 0], [0, 1, 2]]], np.float32)
+    for theta in (0.9, 2.0):
+        compare(custom(f"W6_theta{theta}", z6, [[0, 1]], [[-1, 0]], theta, 1.0, u=[[0, 0.999, 0.5]]), screened=False)
+
+
+# ----------------------------------------------------------------------------- shapes: ragged V, tiny V, many splits, extremes of N
+@pytest.mark.parametrize("dtype,V", [("f32", 32003), ("bf16", 50001), ("bf16", 4104), ("f32", 1030), ("bf16", 33)])
+@pytest.mark.parametrize("T", [0.0, 0.8])
+def test_ragged_vocab(dtype, V, T):
+    w = make_workload(f"ragged_{dtype}_V{V}_T{T}", B=3, N=7, V=V, dtype=dtype, temperature=T,
+                      tree={"kind": "tree", "depth": 3, "max_children": 3}, plant_frac=0.5, seed=V + int(T * 10))
+    compare(w)
+
+
+@pytest.mark.parametrize("V", [2, 3, 5, 8, 9])
+def test_tiny_vocab_all_modes(V):
+    rng = np.random.default_rng(V)
+    B, N = 8, 5
+    z = (rng.integers(0, 9, size=(B, N, V)) * 0.5 + 6).astype(np.float32)
+    par = np.stack([random_tree(rng, N, 2, 3) for _ in range(B)])
+    tok = rng.integers(0, V, size=(B, N)).astype(np.int32)
+    u = rng.random((B, N + 1)).astype(np.float32)
+    q = rng.dirichlet(np.ones(V) * 2, size=(B, N)).astype(np.float32)
+    compare(custom(f"tinyV{V}_greedy", z, tok, par, 0.9, 0.0))
+    compare(custom(f"tinyV{V}_onehot", z, tok, par, 0.9, 1.0, u=u.copy()))
+    compare(custom(f"tinyV{V}_dense", z, tok, par, 0.9, 0.7, u=u.copy(), q=q))
+    compare(custom(f"tinyV{V}_bf16_dense_bf16q", f32_to_bf16_bits(z), tok, par, 0.9, 0.7, u=u.copy(),
+                   q=f32_to_bf16_bits(q)))
+
+
+def test_root_only_request():
+    rng = np.random.default_rng(1)
+    z = (rng.standard_normal((4, 1, 3000)) * 3).astype(np.float32)
+    par = np.full((4, 1), -1, np.int32)
+    tok = np.zeros((4, 1), np.int32)
+    compare(custom("N1_greedy", z, tok, par, 0.9, 0.0))
+    compare(custom("N1_sampling", z, tok, par, 0.9, 1.0, u=rng.random((4, 2)).astype(np.float32)))
+
+
+@pytest.mark.parametrize("T", [0.0, 1.0])
+def test_maximum_nodes(T):
+    """N = MARS_MAX_NODES: a 1024-node chain whose first 700 drafts are accepted, and a bushy tree."""
+    rng = np.random.default_rng(5)
+    N, V = 1024, 96
+    z = (rng.standard_normal((2, N, V)) * 3).astype(np.float32)
+    z[:, :, 7] = 40.0  # token 7 dominates every row: p(7) ~ 1
+    par = np.stack([chain_parents(N), random_tree(rng, N, 9, 4)])
+    tok = np.full((2, N), 7, np.int32)
+    tok[0, 701] = 3
+    tok[1, rng.integers(1, N, 300)] = 5
+    u = (rng.random((2, N + 1)) * 0.9).astype(np.float32)
+    compare(custom(f"maxN_T{T}", z, tok, par, 0.9, T, u=u if T > 0 else None))
+
+
+def test_n_above_maximum_is_rejected():
+    from paper_2601_15498_amd import binding as M
+    assert M.mars_workspace_bytes(1, M.MARS_MAX_NODES + 1, 100) == 0
+    with pytest.raises(M.MarsError):
+        M.alloc_workspace(1, M.MARS_MAX_NODES + 1, 100)
+
+
+# ----------------------------------------------------------------------------- ties, masks, domains
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_heavy_ties_across_lanes_waves_and_splits(dtype):
+    """A coarse grid makes the maximum appear many times per row, in different lanes, waves,
+    batches and splits: id1 / id2 must still be the two lowest indices holding it."""
+    rng = np.random.default_rng(17)
+    B, N, V = 4, 6, 40000
+    z = np.round(rng.standard_normal((B, N, V)) * 2).astype(np.float32) + 20
+    z[0, 0, :] = 5.0                      # a constant row: every lane is a candidate
+    z[0, 1, :] = 1.0
+    z[0, 1, [39999, 20000]] = 30.0        # two equal maxima far apart
+    z[0, 2, :] = 2.0
+    z[0, 2, 1234] = 9.0                   # a single maximum, runner-up tied everywhere
+    z[0, 3, :4] = [50, 50, 50, 50]        # duplicates inside one 16-byte vector
+    logits = f32_to_bf16_bits(z) if dtype == "bf16" else z
+    par = np.stack([random_tree(rng, N, 3, 3) for _ in range(B)])
+    order = np.argsort(-z, axis=2, kind="stable")[:, :, :2]
+    tok = np.zeros((B, N), np.int32)
+    for b in range(B):
+        for i in range(1, N):
+            tok[b, i] = order[b, par[b, i], rng.integers(2)]
+    u = rng.random((B, N + 1)).astype(np.float32)
+    compare(custom(f"ties_{dtype}_greedy", logits, tok, par, 0.9, 0.0))
+    compare(custom(f"ties_{dtype}_sampling", logits, tok, par, 0.9, 2.0, u=u))
+
+
+def test_masked_and_negative_rows():
+    rng = np.random.default_rng(23)
+    B, N, V = 2, 6, 20000
+    z = (rng.standard_normal((B, N, V)) * 3).astype(np.float32)
+    z[0, 0, :] = -np.inf
+    z[0, 0, [77, 15000]] = [3.0, 2.9]      # everything masked but two tokens
+    z[0, 1, :] = -np.inf
+    z[0, 1, 19999] = 1.0                    # a single live token: runner-up is -inf at index 0
+    z[0, 2, :] = -np.inf
+    z[0, 2, 0] = 4.0                        # ... and when the live token is index 0 the runner-up is index 1
+    z[0, 3] = -np.abs(z[0, 3]) - 1.0        # all-negative row: no relaxation whatever the ratio
+    z[1, 0, ::2] = -np.inf                  # half the vocabulary masked
+    par = np.tile(np.array([-1, 0, 0, 1, 2, 3], np.int32), (B, 1))
+    tok = np.array([[0, 77, 15000, 19999, 0, 5], [0, 1, 3, 5, 7, 9]], np.int32)
+    u = rng.random((B, N + 1)).astype(np.float32)
+    compare(custom("masked_greedy", z, tok, par, 0.9, 0.0))
+    compare(custom("masked_sampling", z, tok, par, 0.9, 1.0, u=u))
+    compare(custom("masked_bf16", f32_to_bf16_bits(z), tok, par, 0.9, 1.0, u=u.copy()))
+
+
+@pytest.mark.parametrize("T", [0.05, 0.3, 4.0])
+def test_temperature_extremes(T):
+    w = make_workload(f"temp_{T}", B=4, N=10, V=30008, dtype="bf16", temperature=T,
+                      tree={"kind": "tree", "depth": 4, "max_children": 3}, plant_frac=0.5, seed=int(T * 100))
+    compare(w)
+
+
+def test_large_logit_range_rescales_the_reference():
+    """Rows whose running maximum keeps rising by large steps force the sum-exp reference to move."""
+    rng = np.random.default_rng(31)
+    B, N, V = 2, 4, 70000
+    z = (rng.standard_normal((B, N, V)) * 3).astype(np.float32)
+    z[:, :, :] += np.linspace(-300, 300, V, dtype=np.float32)[None, None, :]   # steadily rising
+    z[1] = z[1, :, ::-1]                                                        # steadily falling
+    par = np.tile(np.array([-1, 0, 1, 1], np.int32), (B, 1))
+    tok = np.array([[0, V - 1, V - 2, 5], [0, 0, 1, 2]], np.int32)
+    u = rng.random((B, N + 1)).astype(np.float32)
+    compare(custom("rising_T1", z, tok, par, 0.9, 1.0, u=u))
+    compare(custom("rising_T0.1", z, tok, par, 0.9, 0.1, u=u.copy()))
+
+
+# ----------------------------------------------------------------------------- malformed requests, determinism, misalignment
+def test_malformed_requests_get_status_and_fallback():
+    w = make_workload("malformed", B=6, N=8, V=5000, dtype="f32", temperature=0.0,
+                      tree={"kind": "tree", "depth": 3, "max_children": 3}, seed=99)
+    w.tree_parent[1, 3] = 5          # parent after child
+    w.tree_parent[2, 0] = 0          # root must carry -1
+    w.draft_tokens[3, 2] = w.V       # token out of range
+    w.draft_tokens[4, 4] = -1
+    w.draft_tokens[5, 0] = -12345    # the root token is never read
+    s = compare(w)
+    w.temperature = 0.9
+    w.uniforms = np.random.default_rng(3).random((6, 9)).astype(np.float32)
+    compare(w, label="malformed_sampling")
+
+
+def test_repeated_calls_are_identical():
+    w = make_config(2, B=2)
+    from oracle import screen
+    screen.screen_uniforms(w)
+    d = to_device(w)
+    first = run_gpu(w, d)
+    keep = {k: getattr(first, k).clone() for k in ("accept_len", "bonus_token", "path_idx", "stats", "diag")}
+    for rep in range(10):
+        out = run_gpu(w, d)
+        for k, v in keep.items():
+            assert torch.equal(getattr(out, k), v), f"call {rep}: {k} changed"
+
+
+def test_rows_not_16_byte_aligned_base():
+    """A logits view that starts 2 or 4 bytes into an allocation takes the element-wise path."""
+    from paper_2601_15498_amd import binding as M
+    from oracle import mars_ref
+    rng = np.random.default_rng(41)
+    B, N, V = 2, 3, 8192
+    z = (rng.standard_normal((B, N, V)) * 3).astype(np.float32)
+    big = torch.empty(B * N * V + 8, dtype=torch.float32, device="cuda")
+    view = big[1:1 + B * N * V].view(B, N, V)
+    view.copy_(torch.from_numpy(z))
+    theta = torch.full((B,), 0.9, device="cuda")
+    st = M.mars_row_stats(view, theta, 1.0)
+    torch.cuda.synchronize()
+    from tests.gpu_util import assert_stats_match
+    assert_stats_match(st, mars_ref.row_stats(z, 0.9, 1.0), True, "misaligned_base")
