@@ -7,10 +7,15 @@ its own, the uniforms of every request whose smallest decision margin (as the
 oracle reports it) is below ``guard``:
 
 * acceptance tests (Eq. 1):  |u - f(x)/q(x)| >= guard;
-* the final inverse-CDF draw: u * sum(f) at least ``guard`` * sum(f) away from
-  the CDF steps on either side of the chosen token;
-* residual normalisers Z >= ``min_norm`` (an ill-conditioned renormalisation
-  would magnify fp32 rounding past the guard band).
+* the final inverse-CDF draw: u * sum(f) at least ``cdf_guard`` * sum(f) away from
+  the CDF steps on either side of the chosen token (``cdf_guard`` defaults to ``guard``;
+  a flat distribution over a large vocabulary has no token wider than 2e-4 and needs a
+  narrower band, which is sound as long as it stays well above the fp32 error of a
+  normalised prefix sum, a few 1e-7);
+* residual normalisers Z >= ``min_norm``: Z is a difference of probability masses of
+  order 1, so an fp32 evaluation carries an absolute error of a few 1e-7 whatever its
+  size, and the next acceptance probability inherits the relative error 1e-7/Z; below
+  about 1e-2 that would come within reach of the guard band.
 
 The path may change after a re-draw, so the oracle is run again until every
 request is clean.  Returns the oracle's output for the final uniforms.
@@ -24,18 +29,20 @@ def _sub(a, idx):
     return None if a is None else np.ascontiguousarray(a[idx])
 
 
-def screen_uniforms(w, guard: float = 1e-4, min_norm: float = 1e-3, max_rounds: int = 200,
-                    seed: int = 987654321):
+def screen_uniforms(w, guard: float = 1e-4, min_norm: float = 2e-2, max_rounds: int = 200,
+                    seed: int = 987654321, cdf_guard: float = None):
     """``w`` is a workload object with numpy fields (logits, draft_tokens, tree_parent, theta,
     temperature, uniforms, draft_probs); ``w.uniforms`` is updated in place."""
     out = mars_ref.verify(w.logits, w.draft_tokens, w.tree_parent, w.theta, w.temperature,
                           w.uniforms, w.draft_probs)
     if not w.temperature > 0:
         return out
+    if cdf_guard is None:
+        cdf_guard = guard
     rounds = 0
     while True:
         d = out["diag"]
-        bad = np.nonzero((d["min_accept_margin"] < guard) | (d["min_cdf_margin"] < guard)
+        bad = np.nonzero((d["min_accept_margin"] < guard) | (d["min_cdf_margin"] < cdf_guard)
                          | (d["min_norm"] < min_norm))[0]
         if bad.size == 0:
             return out

@@ -228,7 +228,7 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   __shared__ int32_t sh_ctok[MARS_MAX_NODES];    // residual chain: rejected tokens
   __shared__ float sh_cinv[MARS_MAX_NODES];      // residual chain: 1/Z
   __shared__ double sh_red[NW];
-  __shared__ float sh_tile[kMaxTiles];
+  __shared__ double sh_tile[kMaxTiles];
   __shared__ int sh_accept;                      // decision code of the child under test
 
   const int b = blockIdx.x;
@@ -368,13 +368,13 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
 
   for (int t = 0; t < tiles_per_wave; ++t) {
     const int tile = wave * tiles_per_wave + t;
-    float acc = 0.0f;
+    double acc = 0.0;
     for (int r = 0; r < rep; ++r) {
       const int g = tile_step_group(tile, r);
       if (g < ngroups) {
         float f[8];
         group_values(g, f);
-        acc += ((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7]));
+        acc += static_cast<double>(((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7])));
       }
     }
     acc = wave_sum(acc);
@@ -387,7 +387,7 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
     double mine = 0.0;
     for (int i = 0; i < per_lane; ++i) {
       const int t = lane * per_lane + i;
-      if (t < ntiles) mine += static_cast<double>(sh_tile[t]);
+      if (t < ntiles) mine += sh_tile[t];
     }
     double incl = mine;  // inclusive scan over lanes
 #pragma unroll
@@ -410,7 +410,7 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
       for (int i = 0; i < per_lane; ++i) {
         const int t = L * per_lane + i;
         if (t >= ntiles) break;
-        const double nxt = cum + static_cast<double>(sh_tile[t]);
+        const double nxt = cum + sh_tile[t];
         if (nxt > target) { tile = t; break; }
         cum = nxt;
       }

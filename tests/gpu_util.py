@@ -2,7 +2,10 @@
 binding) and through the CPU oracle, and compare element by element.
 
 Bar: decisions, lengths, paths, tokens, indices and the top-2 logit values are bit-exact;
-fp32 statistics (sum-exp, residual normaliser, bonus probability) agree within rel 1e-5.
+fp32 statistics (sum-exp, bonus probability) agree within rel 1e-5.  The residual normaliser
+Z = sum max(0, f - q) is a difference of probability masses of order 1: each f(v) is an fp32
+number with a few ulp of relative error, so Z carries an absolute error of up to about
+8 ulp(1) ~ 1e-6 however small it is; its tolerance is rel 1e-5 plus that absolute floor.
 """
 import sys
 
@@ -13,6 +16,7 @@ from oracle import mars_ref, screen
 from paper_2601_15498_amd import binding as M
 
 REL_TOL = 1e-5
+RESIDUAL_ABS_TOL = 1e-6
 
 
 def say(msg):
@@ -58,13 +62,13 @@ def assert_stats_match(stats_gpu, ref_stats, sampling, label=""):
     return 0.0
 
 
-def compare(w, label=None, screened=True):
+def compare(w, label=None, screened=True, cdf_guard=None):
     """Run both sides on workload ``w`` (uniforms are screened in place first) and assert parity.
     Returns a small summary dict."""
     label = label or w.name
     say(f"[case] {label}: B={w.B} N={w.N} V={w.V} dtype={w.dtype} T={w.temperature} "
         f"dense_q={w.draft_probs is not None}")
-    ref = screen.screen_uniforms(w) if screened else mars_ref.verify(
+    ref = screen.screen_uniforms(w, cdf_guard=cdf_guard) if screened else mars_ref.verify(
         w.logits, w.draft_tokens, w.tree_parent, w.theta, w.temperature, w.uniforms, w.draft_probs)
     out = run_gpu(w)
     sampling = w.temperature > 0
@@ -83,7 +87,8 @@ def compare(w, label=None, screened=True):
         assert np.array_equal(dg["residual_passes"][ok], rd["residual_passes"][ok]), f"{label}: residual_passes"
         for key in ("bonus_prob", "last_residual_norm"):
             a, b = dg[key][ok].astype(np.float64), rd[key][ok]
-            rel = np.abs(a - b) / np.maximum(np.abs(b), 1e-30)
+            floor = RESIDUAL_ABS_TOL if key == "last_residual_norm" else 0.0
+            rel = np.maximum(np.abs(a - b) - floor, 0.0) / np.maximum(np.abs(b), 1e-30)
             rel[(a == 0) & (b == 0)] = 0
             assert rel.max(initial=0) <= REL_TOL, f"{label}: {key} rel err {rel.max():.3e} at request {rel.argmax()}"
             d_err = max(d_err, float(rel.max(initial=0)))
