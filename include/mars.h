@@ -114,7 +114,16 @@ const char* mars_status_string(int status);
 size_t mars_workspace_bytes(int B, int N, int V);
 
 /*
- * Row reduction only (Sec. 3.3 top-2, Eq. 3 sum-exp, Eq. 4 ratio test):
+ * First stage only: the streaming row reduction (Sec. 3.3 top-2 identification, Eq. 3
+ * max / sum-exp) into per-(row, split) partial results inside the workspace.  This is the
+ * HBM-bound kernel of the pass; the entry point exists so that it can be timed by itself.
+ * Arguments as for mars_row_stats.  Returns MARS_OK or a negative code.
+ */
+int mars_row_reduce(const void* logits, int logits_dtype, float temperature, int B, int N, int V,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Row reduction and merge (Sec. 3.3 top-2, Eq. 3 sum-exp, Eq. 4 ratio test):
  * fills stats[B*N].  temperature == 0 skips the sum-exp (sum_exp = 0).
  *
  *   logits       device, [B,N,V] row-major, element type logits_dtype, rows contiguous
@@ -158,7 +167,7 @@ int mars_row_stats(const void* logits, int logits_dtype, const float* theta,
  *                 request with a non-zero status gets accept_len = 0, an empty path
  *                 and bonus_token = v(1) of its root row.
  *   stats         device out, optional (NULL ok), [B*N] row statistics.
- *   diag          device out, optional (NULL ok), [B]; zero-filled in greedy mode.
+ *   diag          device out, optional (NULL ok), [B]; in greedy mode only last_node is set.
  *   workspace     device, >= mars_workspace_bytes(B,N,V), 256-byte aligned.
  *   hip_stream    hipStream_t (NULL = default stream).
  *

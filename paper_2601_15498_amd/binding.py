@@ -37,6 +37,9 @@ def lib():
         L.mars_status_string.argtypes = [ctypes.c_int]
         L.mars_workspace_bytes.restype = ctypes.c_size_t
         L.mars_workspace_bytes.argtypes = [ctypes.c_int] * 3
+        L.mars_row_reduce.restype = ctypes.c_int
+        L.mars_row_reduce.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_int, ctypes.c_int,
+                                      ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.mars_row_stats.restype = ctypes.c_int
         L.mars_row_stats.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_float,
                                      ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
@@ -90,6 +93,14 @@ def alloc_workspace(B: int, N: int, V: int, device="cuda") -> torch.Tensor:
     if n == 0:
         raise MarsError(f"sizes out of range: B={B} N={N} V={V}")
     return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def mars_row_reduce(logits: torch.Tensor, temperature: float, workspace: torch.Tensor) -> None:
+    """First stage only (the streaming row reduction); partial results stay in the workspace."""
+    B, N, V = logits.shape
+    assert logits.is_contiguous()
+    _check(lib().mars_row_reduce(_ptr(logits), _dtype_code(logits), float(temperature), B, N, V,
+                                 _ptr(workspace), workspace.numel(), _stream()))
 
 
 def mars_row_stats(logits: torch.Tensor, theta: torch.Tensor, temperature: float, stats: torch.Tensor = None,

@@ -23,10 +23,16 @@ __device__ __forceinline__ float widen(bf16_t h) { return __uint_as_float(static
 // compile-time element access.
 template <typename T, int EPV> struct Vec;
 
+// The logits are read exactly once per call: the streaming loads carry the non-temporal hint so
+// that they do not displace each other in the caches on their way through.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 template <> struct Vec<bf16_t, 8> {
   uint4 r;
   __device__ __forceinline__ void load(const bf16_t* row, unsigned int vec) {
-    r = reinterpret_cast<const uint4*>(row)[vec];
+    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row) + vec);
+    r = make_uint4(t.x, t.y, t.z, t.w);
   }
   __device__ __forceinline__ void fill_neg_inf() { r = make_uint4(0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u); }
   __device__ __forceinline__ float get(int e) const {
@@ -38,7 +44,7 @@ template <> struct Vec<bf16_t, 8> {
 
 template <> struct Vec<bf16_t, 1> {
   bf16_t r;
-  __device__ __forceinline__ void load(const bf16_t* row, unsigned int vec) { r = row[vec]; }
+  __device__ __forceinline__ void load(const bf16_t* row, unsigned int vec) { r = __builtin_nontemporal_load(row + vec); }
   __device__ __forceinline__ void fill_neg_inf() { r = 0xFF80u; }
   __device__ __forceinline__ float get(int) const { return widen(r); }
 };
@@ -46,7 +52,8 @@ template <> struct Vec<bf16_t, 1> {
 template <> struct Vec<float, 4> {
   float4 r;
   __device__ __forceinline__ void load(const float* row, unsigned int vec) {
-    r = reinterpret_cast<const float4*>(row)[vec];
+    const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(row) + vec);
+    r = make_float4(t.x, t.y, t.z, t.w);
   }
   __device__ __forceinline__ void fill_neg_inf() { r = make_float4(neg_inf(), neg_inf(), neg_inf(), neg_inf()); }
   __device__ __forceinline__ float get(int e) const { return e == 0 ? r.x : e == 1 ? r.y : e == 2 ? r.z : r.w; }
@@ -54,7 +61,7 @@ template <> struct Vec<float, 4> {
 
 template <> struct Vec<float, 1> {
   float r;
-  __device__ __forceinline__ void load(const float* row, unsigned int vec) { r = row[vec]; }
+  __device__ __forceinline__ void load(const float* row, unsigned int vec) { r = __builtin_nontemporal_load(row + vec); }
   __device__ __forceinline__ void fill_neg_inf() { r = neg_inf(); }
   __device__ __forceinline__ float get(int) const { return r; }
 };
@@ -85,44 +92,70 @@ __device__ __forceinline__ void top2_insert(unsigned long long& k1, unsigned lon
 }
 
 // ---------------------------------------------------------------- wave-level reductions (wave64)
+// Butterfly inside each row of 16 lanes with DPP (no LDS traffic): xor 1 and xor 2 by quad
+// permutes, then the two mirrors; the four row results are combined through readlane.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7 - i inside each group of 8
+constexpr int kDppMirror = 0x140;      // lane i <-> 15 - i inside each row of 16
+
+__device__ __forceinline__ float lane_value(float v, int lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
-  return v;
+  v = fmaxf(v, dpp_move<kDppXor1>(v));
+  v = fmaxf(v, dpp_move<kDppXor2>(v));
+  v = fmaxf(v, dpp_move<kDppHalfMirror>(v));
+  v = fmaxf(v, dpp_move<kDppMirror>(v));
+  return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
 }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
-  return v;
+  v += dpp_move<kDppXor1>(v);
+  v += dpp_move<kDppXor2>(v);
+  v += dpp_move<kDppHalfMirror>(v);
+  v += dpp_move<kDppMirror>(v);
+  return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
 }
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
   return v;
 }
-// Merge value-only top-2 pairs (a1 >= a2) across the wave: the two largest values
-// of the union, with multiplicity.
+// Two largest values (with multiplicity) of the union of two pairs a1 >= a2, b1 >= b2.
+__device__ __forceinline__ void top2_merge_values(float& a1, float& a2, float b1, float b2) {
+  const float lo = fminf(a1, b1);
+  a1 = fmaxf(a1, b1);
+  a2 = fmaxf(lo, fmaxf(a2, b2));
+}
+// Merge value-only top-2 pairs (a1 >= a2) across the wave.
 __device__ __forceinline__ void wave_top2_values(float& a1, float& a2) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) {
-    const float b1 = __shfl_xor(a1, m, kWave);
-    const float b2 = __shfl_xor(a2, m, kWave);
-    const float lo = fminf(a1, b1);
-    a1 = fmaxf(a1, b1);
-    a2 = fmaxf(lo, fmaxf(a2, b2));
-  }
+  top2_merge_values(a1, a2, dpp_move<kDppXor1>(a1), dpp_move<kDppXor1>(a2));
+  top2_merge_values(a1, a2, dpp_move<kDppXor2>(a1), dpp_move<kDppXor2>(a2));
+  top2_merge_values(a1, a2, dpp_move<kDppHalfMirror>(a1), dpp_move<kDppHalfMirror>(a2));
+  top2_merge_values(a1, a2, dpp_move<kDppMirror>(a1), dpp_move<kDppMirror>(a2));
+  float r1 = lane_value(a1, 0), r2 = lane_value(a2, 0);
+  top2_merge_values(r1, r2, lane_value(a1, 16), lane_value(a2, 16));
+  top2_merge_values(r1, r2, lane_value(a1, 32), lane_value(a2, 32));
+  top2_merge_values(r1, r2, lane_value(a1, 48), lane_value(a2, 48));
+  a1 = r1; a2 = r2;
 }
 
 // Per-(row, split) partial result of the row reduction.  id < 0 marks an absent
 // candidate (a split with fewer than two elements).  s is the partial sum of
-// exp2((z - z1) * c) over the split, relative to the split's own z1.
+// exp2(z * c - ref) over the split; ref is integer-valued, so that sums taken against
+// different references are brought together by exact power-of-two scalings.
 struct Partial {
   float   z1;
   int32_t id1;
   float   z2;
   int32_t id2;
   float   s;
-  int32_t pad;
+  float   ref;
 };
 
 // Merge the splits of one row into the public statistics entry.
@@ -137,10 +170,13 @@ __device__ __forceinline__ void merge_row(const Partial* __restrict__ p, int spl
   const float z1 = key_value(k1), z2 = key_value(k2);
   double S = 0.0;
   if (c > 0.0f) {
+    float R = -3.0e38f;
     for (int s = 0; s < splits; ++s)
-      if (p[s].s > 0.0f)
-        S += static_cast<double>(p[s].s) *
-             exp2((static_cast<double>(p[s].z1) - static_cast<double>(z1)) * static_cast<double>(c));
+      if (p[s].s > 0.0f) R = fmaxf(R, p[s].ref);
+    for (int s = 0; s < splits; ++s)
+      if (p[s].s > 0.0f) S += ldexp(static_cast<double>(p[s].s), static_cast<int>(fmaxf(p[s].ref - R, -2000.0f)));
+    // S is relative to the integer reference R; move it to the row maximum (|R - z1*c| is small)
+    S *= exp2(static_cast<double>(R) - static_cast<double>(z1) * static_cast<double>(c));
   }
   mars_row_stat st;
   st.z1 = z1; st.id1 = key_index(k1);

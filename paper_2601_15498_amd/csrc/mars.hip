@@ -104,6 +104,23 @@ size_t mars_workspace_bytes(int B, int N, int V) {
   return mars::layout(B, N, V).total;
 }
 
+int mars_row_reduce(const void* logits, int logits_dtype, float temperature, int B, int N, int V, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+  using namespace mars;
+  if (!logits) return MARS_ERR_ARG;
+  if (!sizes_ok(B, N, V)) return MARS_ERR_ARG;
+  if (!(temperature >= 0.0f) || std::isinf(temperature)) return MARS_ERR_ARG;
+  if (logits_dtype != MARS_F32 && logits_dtype != MARS_BF16) return MARS_ERR_DTYPE;
+  const Layout L = layout(B, N, V);
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0 || workspace_bytes < L.total)
+    return MARS_ERR_WORKSPACE;
+  Partial* partials = reinterpret_cast<Partial*>(static_cast<char*>(workspace) + L.partials_off);
+  const hipError_t e = launch_row_reduce(logits, logits_dtype, static_cast<long>(B) * N, V, L.splits,
+                                         temperature > 0.0f, log2e_over_t(temperature), partials,
+                                         static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MARS_OK : MARS_ERR_HIP;
+}
+
 int mars_row_stats(const void* logits, int logits_dtype, const float* theta, float temperature, int B, int N, int V,
                    mars_row_stat* stats, void* workspace, size_t workspace_bytes, void* hip_stream) {
   using namespace mars;

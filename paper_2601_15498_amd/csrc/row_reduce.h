@@ -1,12 +1,14 @@
 // Row reduction: per (row, split) the two largest logits with their indices under
-// (value desc, index asc) and, in sampling mode, the sum of exp((z - ref)/T).
+// (value desc, index asc) and, in sampling mode, the sum of exp2(z*c - ref).
 // One streaming read of the logits; this is the HBM-bound kernel of the pass
 // (paper Sec. 3.3 top-2 identification, Eq. 3 softmax normaliser).
 //
-// Per element the lane does value-only work: widen, a (max, second max) update and,
-// when sampling, one fma + exp2 + add.  Indices are recovered afterwards: each lane
-// remembers in which batch its two best values first appeared, and only the few
-// lanes that hold a row-level candidate reload that one batch to find the position.
+// The per-element work is kept to the minimum the arithmetic units can hide behind the
+// memory stream: widen, half a max3 and, when sampling, one fma + exp2 + add.  A lane only
+// tracks the maxima of its batches (32 elements each): the best and second-best batch
+// maximum and the batches they came from.  A lane's two largest elements are then known to
+// lie in those two batches, so after the stream the few lanes that can hold a row-level
+// candidate reload one or two batches and produce exact (value, index) pairs.
 #pragma once
 
 #include "common.h"
@@ -15,35 +17,25 @@ namespace mars {
 
 constexpr int kRowThreads = 256;  // 4 waves per work-group
 constexpr int kUnroll = 4;        // 16-byte loads per lane per batch
-constexpr float kRescaleLog2 = 24.0f;  // rescale the sum-exp reference when the max rises by 2^24
+constexpr float kRescaleLog2 = 24.0f;  // move the sum-exp reference when the max rises by 2^24
 
-// (m1 >= m2) <- the two largest of {m1, m2, x}: m2 = median(m1, m2, x), m1 = max(m1, x).
-// Written as one two-instruction block so that the pair stays together: left to itself the
-// scheduler hoists the whole max chain and keeps every intermediate maximum alive for the
-// medians, which triples the register count of the loop.
-__device__ __forceinline__ void top2_update(float& m1, float& m2, float x) {
-  asm("v_med3_f32 %1, %0, %1, %2\n\tv_max_f32 %0, %0, %2" : "+v"(m1), "+v"(m2) : "v"(x));
-}
-
-// Position (within the lane's batch) of the first element equal to `target`, other than
-// position `skip`; -1 if none.  Positions are j * EPV + e, ascending in vocabulary index.
+// Exact (value desc, index asc) top-2 among the elements of the lane's batch `batch` whose
+// value is >= cut, merged into (k1, k2).
 template <typename T, int EPV>
-__device__ int find_in_batch(const T* __restrict__ rowp, int v_begin, int v_end, int batch, int tid,
-                             float target, int skip) {
-  int found = -1;
-  for (int j = kUnroll - 1; j >= 0; --j) {
+__device__ void scan_batch(const T* __restrict__ rowp, int v_begin, int v_end, int batch, int tid, float cut,
+                           unsigned long long& k1, unsigned long long& k2) {
+  for (int j = 0; j < kUnroll; ++j) {
     const int vec = v_begin + (batch * kUnroll + j) * kRowThreads + tid;
     if (vec < v_end) {
       Vec<T, EPV> v;
-      v.load(rowp, vec);
+      v.load(rowp, static_cast<unsigned int>(vec));
 #pragma unroll
-      for (int e = EPV - 1; e >= 0; --e) {
-        const int pos = j * EPV + e;
-        if (v.get(e) == target && pos != skip) found = pos;
+      for (int e = 0; e < EPV; ++e) {
+        const float x = v.get(e);
+        if (x >= cut) top2_insert(k1, k2, make_key(x, vec * EPV + e));
       }
     }
   }
-  return found;
 }
 
 template <typename T, int EPV, bool SAMPLING>
@@ -52,6 +44,8 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
                                                                   Partial* __restrict__ partials) {
   constexpr int U = kUnroll;
   constexpr int BV = kRowThreads * U;  // vectors per batch
+  constexpr int NE = U * EPV;          // elements per lane per batch
+  constexpr int NW = kRowThreads / kWave;
   const int item = blockIdx.x;
   const int row = item / splits;
   const int split = item - row * splits;
@@ -64,11 +58,11 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   const int nb = (nv + BV - 1) / BV;
   const int nfull = nv / BV;  // batches that need no bounds check
 
-  float m1 = neg_inf(), m2 = neg_inf();  // the lane's two largest values so far (with multiplicity)
-  int b1 = -1, b2 = -1;                  // batch in which each first appeared
+  float m1 = neg_inf(), m2 = neg_inf();  // best and second-best batch maximum of this lane
+  int b1 = -1, b2 = -1;                  // the (distinct) batches they belong to
   float s = 0.0f;                        // sum of exp2(z*c - ref_c) over the lane's elements
-  float ref_c = -1.0e30f;                // wave-uniform reference, already multiplied by c
-  float thresh = -3.0e38f;               // rescale when a lane max exceeds this (wave-uniform)
+  float ref_c = -1.0e30f;                // wave-uniform, integer-valued reference (already times c)
+  float thresh = -3.0e38f;               // rescale when a lane maximum exceeds this (wave-uniform)
   const float tau_over_c = SAMPLING ? kRescaleLog2 / c : 0.0f;
 
   Vec<T, EPV> bufA[U], bufB[U];
@@ -84,33 +78,47 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
 #pragma unroll
     for (int j = 0; j < U; ++j) {
       const int vec = base + j * kRowThreads;
-      if (vec < v_end) buf[j].load(rowp, vec); else buf[j].fill_neg_inf();
+      if (vec < v_end) buf[j].load(rowp, static_cast<unsigned int>(vec)); else buf[j].fill_neg_inf();
     }
   };
 
   auto process = [&](const Vec<T, EPV>(&buf)[U], int k) {
-    const float o1 = m1, o2 = m2;
-    float x[U * EPV];
+    float x[NE];
 #pragma unroll
     for (int j = 0; j < U; ++j)
 #pragma unroll
       for (int e = 0; e < EPV; ++e) x[j * EPV + e] = buf[j].get(e);
+    // batch maximum: max3 over pairs, two independent chains
+    float bm;
+    if (NE >= 4) {
+      float ma = fmaxf(x[0], x[1]), mb = fmaxf(x[2], x[3]);
 #pragma unroll
-    for (int i = 0; i < U * EPV; ++i) top2_update(m1, m2, x[i]);
-    // Where did the lane's two best values first appear?  A new maximum demotes the old one,
-    // whose first occurrence stays where it was; anything else that raises m2 is in this batch.
-    const bool gt = m1 > o1;
-    const bool ch2 = m2 > o2;
-    const int nb2 = (gt && m2 == o1) ? b1 : k;
-    b2 = ch2 ? nb2 : b2;
+      for (int i = 4; i + 3 < NE; i += 4) {
+        ma = fmaxf(fmaxf(ma, x[i]), x[i + 1]);
+        mb = fmaxf(fmaxf(mb, x[i + 2]), x[i + 3]);
+      }
+      bm = fmaxf(ma, mb);
+    } else {
+      bm = x[0];
+#pragma unroll
+      for (int i = 1; i < NE; ++i) bm = fmaxf(bm, x[i]);
+    }
+    // Best and second-best batch maximum, first occurrence wins ties (later batches have
+    // higher vocabulary indices).  A new best demotes the old one.
+    const bool gt = bm > m1;
+    const bool g2 = bm > m2;
+    m2 = gt ? m1 : (g2 ? bm : m2);
+    b2 = gt ? b1 : (g2 ? k : b2);
+    m1 = gt ? bm : m1;
     b1 = gt ? k : b1;
     if (SAMPLING) {
       if (__any(m1 > thresh)) {
-        // Rare: the wave's maximum rose by more than 2^kRescaleLog2 above the reference (or this
-        // is the wave's first batch).  Move the reference to the wave maximum before any term of
-        // this batch is formed, so that no exponent ever exceeds kRescaleLog2.
+        // Rare: the wave's maximum rose more than 2^kRescaleLog2 above the reference (or this is
+        // the wave's first batch).  Move the reference up to the wave maximum, rounded up to an
+        // integer, before any term of this batch is formed: no exponent ever exceeds
+        // kRescaleLog2, and references differ by exact powers of two.
         const float wm = wave_max(m1);
-        const float new_ref_c = wm * c;
+        const float new_ref_c = __builtin_ceilf(wm * c);
         s *= __builtin_amdgcn_exp2f(ref_c - new_ref_c);
         ref_c = new_ref_c;
         thresh = wm + tau_over_c;
@@ -159,9 +167,8 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   }
 
   // ------------------------------------------------------------------ work-group epilogue
-  __shared__ float sh_m1[kRowThreads / kWave], sh_m2[kRowThreads / kWave];
-  __shared__ float sh_ref[kRowThreads / kWave], sh_sum[kRowThreads / kWave];
-  __shared__ unsigned long long sh_cand[2 * kRowThreads];
+  __shared__ float sh_m1[NW], sh_m2[NW], sh_ref[NW], sh_sum[NW];
+  __shared__ unsigned long long sh_cand[4 * kRowThreads];
   __shared__ int sh_ncand;
 
   const int wave = tid / kWave, lane = tid % kWave;
@@ -175,30 +182,24 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   }
   if (tid == 0) sh_ncand = 0;
   __syncthreads();
-  float Z1 = sh_m1[0], Z2 = sh_m2[0];
+  float Z1 = sh_m1[0], L2 = sh_m2[0];
 #pragma unroll
-  for (int w = 1; w < kRowThreads / kWave; ++w) {
-    const float c1 = sh_m1[w], c2 = sh_m2[w];
-    const float lo = fminf(Z1, c1);
-    Z1 = fmaxf(Z1, c1);
-    Z2 = fmaxf(lo, fmaxf(Z2, c2));
-  }
-  // Z1 >= Z2 are the split's two largest values.  Lanes holding a value >= Z2 recover the
-  // index of that element from the batch they remembered.  -inf entries (masked tokens,
-  // padding) are never searched: among them the order is the index order, known in closed form.
-  const bool finite2 = Z2 > neg_inf();
-  const float cut = finite2 ? Z2 : Z1;
-  if (cut > neg_inf() && m1 >= cut) {
-    const int p1 = find_in_batch<T, EPV>(rowp, v_begin, v_end, b1, tid, m1, -1);
-    const int vec1 = v_begin + (b1 * U + p1 / EPV) * kRowThreads + tid;
-    const int slot = atomicAdd(&sh_ncand, 1);
-    sh_cand[slot] = make_key(m1, vec1 * EPV + p1 % EPV);
-    if (finite2 && m2 >= cut) {
-      const int p2 = find_in_batch<T, EPV>(rowp, v_begin, v_end, b2, tid, m2, b2 == b1 ? p1 : -1);
-      const int vec2 = v_begin + (b2 * U + p2 / EPV) * kRowThreads + tid;
-      const int slot2 = atomicAdd(&sh_ncand, 1);
-      sh_cand[slot2] = make_key(m2, vec2 * EPV + p2 % EPV);
-    }
+  for (int w = 1; w < NW; ++w) top2_merge_values(Z1, L2, sh_m1[w], sh_m2[w]);
+  // Z1 is the split's maximum; L2, the second largest batch maximum over all lanes, is a lower
+  // bound of its runner-up.  Every element >= L2 lies in batch b1 or b2 of a lane whose own
+  // maxima reach L2; those lanes rescan.  -inf entries (masked tokens, padding) are never
+  // searched: among them the order is the index order, known in closed form.
+  // (L2 == -inf only says that a single lane saw finite values in a single batch; the runner-up
+  // may still be finite inside that batch, so the scan then takes every finite element.)
+  const float cut = L2 > neg_inf() ? L2 : -3.4028235e38f;
+  if (Z1 > neg_inf() && m1 >= cut) {
+    unsigned long long k1 = 0, k2 = 0;
+    scan_batch<T, EPV>(rowp, v_begin, v_end, b1, tid, cut, k1, k2);
+    if (m2 >= cut) scan_batch<T, EPV>(rowp, v_begin, v_end, b2, tid, cut, k1, k2);
+    const int n = (k1 != 0) + (k2 != 0);
+    const int slot = atomicAdd(&sh_ncand, n);
+    if (k1 != 0) sh_cand[slot] = k1;
+    if (k2 != 0) sh_cand[slot + 1] = k2;
   }
   __syncthreads();
   if (tid == 0) {
@@ -207,20 +208,23 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
     for (int i = 0; i < n; ++i) top2_insert(k1, k2, sh_cand[i]);
     const int first = v_begin * EPV, count = nv * EPV;
     Partial out;
-    out.z1 = neg_inf(); out.id1 = -1; out.z2 = neg_inf(); out.id2 = -1; out.s = 0.0f; out.pad = 0;
+    out.z1 = neg_inf(); out.id1 = -1; out.z2 = neg_inf(); out.id2 = -1; out.s = 0.0f; out.ref = 0.0f;
     if (count > 0) {
       if (k1 != 0) { out.z1 = key_value(k1); out.id1 = key_index(k1); }
       else { out.id1 = first; }  // every element is -inf
       if (k2 != 0) { out.z2 = key_value(k2); out.id2 = key_index(k2); }
       else if (count > 1) { out.id2 = (out.id1 == first) ? first + 1 : first; }  // runner-up is a -inf entry
     }
-    if (SAMPLING && out.z1 > neg_inf()) {
-      const double z1c = static_cast<double>(out.z1) * static_cast<double>(c);
-      double S = 0.0;
+    if (SAMPLING) {
+      float R = -3.0e38f;
 #pragma unroll
-      for (int w = 0; w < kRowThreads / kWave; ++w)
-        if (sh_sum[w] > 0.0f) S += static_cast<double>(sh_sum[w]) * exp2(static_cast<double>(sh_ref[w]) - z1c);
-      out.s = static_cast<float>(S);
+      for (int w = 0; w < NW; ++w)
+        if (sh_sum[w] > 0.0f) R = fmaxf(R, sh_ref[w]);
+      float S = 0.0f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w)  // exact power-of-two scalings
+        if (sh_sum[w] > 0.0f) S += ldexpf(sh_sum[w], static_cast<int>(fmaxf(sh_ref[w] - R, -300.0f)));
+      out.s = S; out.ref = S > 0.0f ? R : 0.0f;
     }
     partials[item] = out;
   }

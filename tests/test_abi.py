@@ -27,7 +27,7 @@ def declared_functions():
 
 
 def test_header_declares_the_expected_entry_points():
-    assert declared_functions() == ["mars_row_stats", "mars_status_string", "mars_verify", "mars_version",
+    assert declared_functions() == ["mars_row_reduce", "mars_row_stats", "mars_status_string", "mars_verify", "mars_version",
                                     "mars_workspace_bytes"]
 
 
@@ -81,6 +81,11 @@ def test_host_side_argument_errors_enqueue_nothing(lib):
     assert call(ldt=7) == -2
     assert call(T=1.0, u=p, dq=p, ddt=5) == -2
     assert call(ws=null) == -3 and call(wsb=16) == -3 and call(ws=ctypes.c_void_p(0x1010)) == -3
+    rr = lib.mars_row_reduce
+    assert rr(null, 0, ctypes.c_float(0.0), 1, 1, 10, p, ctypes.c_size_t(1 << 20), null) == -1
+    assert rr(p, 9, ctypes.c_float(0.0), 1, 1, 10, p, ctypes.c_size_t(1 << 20), null) == -2
+    assert rr(p, 0, ctypes.c_float(-1.0), 1, 1, 10, p, ctypes.c_size_t(1 << 20), null) == -1
+    assert rr(p, 0, ctypes.c_float(0.0), 1, 1, 10, null, ctypes.c_size_t(1 << 20), null) == -3
     rs = lib.mars_row_stats
     assert rs(null, 0, p, ctypes.c_float(0.0), 1, 1, 10, p, p, ctypes.c_size_t(1 << 20), null) == -1
     assert rs(p, 3, p, ctypes.c_float(0.0), 1, 1, 10, p, p, ctypes.c_size_t(1 << 20), null) == -2
