@@ -64,7 +64,9 @@ enum {
 enum {
   MARS_REQ_OK        = 0,
   MARS_REQ_BAD_TREE  = 1, /* parent[0] != -1, or parent[i] not in [0, i) for i >= 1 */
-  MARS_REQ_BAD_TOKEN = 2  /* draft token of a node i >= 1 outside [0, V) */
+  MARS_REQ_BAD_TOKEN = 2, /* draft token of a node i >= 1 outside [0, V) */
+  MARS_REQ_TIMEOUT   = 3  /* sampling mode: the work-groups sharing this request did not all arrive
+                             (the GPU was not free to run them together); outputs are undefined */
 };
 
 /* decision[b,i] codes (Sec. 3.4 bullets; code 3 is Eq. 1's stochastic accept). */

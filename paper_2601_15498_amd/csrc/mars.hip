@@ -4,6 +4,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 
 #include "../../include/mars.h"
 #include "common.h"
@@ -21,6 +22,7 @@ static size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // Splits per row: a function of (rows, V) only, so that the workspace size does not depend on
 // the element type.
 static int choose_splits(long rows, int V) {
+  if (const char* e = getenv("MARS_SPLITS_TUNE")) { int v = atoi(e); if (v > 0) return v; }
   long want = (kTargetItems + rows - 1) / rows;
   long cap = V / kMinSplitElems;
   if (cap < 1) cap = 1;
@@ -30,9 +32,24 @@ static int choose_splits(long rows, int V) {
 }
 
 struct Layout {
-  int splits;
-  size_t partials_off, stats_off, total;
+  int splits, G;
+  size_t partials_off, stats_off, xslots_off, total;
 };
+
+// Work-groups per request in the sampling tail: enough to spread a request's row passes over
+// the chip when there are few requests, never more than one work-group per compute unit in
+// total (they wait for each other, so all of them must be resident), and every slice at least
+// 4096 vocabulary entries long.
+constexpr int kComputeUnits = 256;
+static int choose_groups(int B, int V) {
+  if (const char* e = getenv("MARS_GROUPS_TUNE")) { int v = atoi(e); if (v > 0) return v > kMaxGroupsPerRequest ? kMaxGroupsPerRequest : v; }
+  int G = kComputeUnits / B;
+  const int cap = V / 4096;
+  if (G > cap) G = cap;
+  if (G > kMaxGroupsPerRequest) G = kMaxGroupsPerRequest;
+  if (G < 1) G = 1;
+  return G;
+}
 
 static Layout layout(int B, int N, int V) {
   Layout L;
@@ -40,7 +57,9 @@ static Layout layout(int B, int N, int V) {
   L.splits = choose_splits(rows, V);
   L.partials_off = 0;
   L.stats_off = align_up(static_cast<size_t>(rows) * L.splits * sizeof(Partial));
-  L.total = L.stats_off + align_up(static_cast<size_t>(rows) * sizeof(mars_row_stat));
+  L.G = choose_groups(B, V);
+  L.xslots_off = L.stats_off + align_up(static_cast<size_t>(rows) * sizeof(mars_row_stat));
+  L.total = L.xslots_off + align_up(static_cast<size_t>(B) * (N + 2) * 2 * L.G * sizeof(unsigned long long));
   return L;
 }
 
@@ -52,30 +71,30 @@ static bool sizes_ok(int B, int N, int V) {
 
 template <typename T, int EPV>
 static hipError_t launch_row_reduce_t(const void* logits, long rows, int V, int splits, bool sampling, float c,
-                                      Partial* partials, hipStream_t stream) {
+                                      Partial* partials, unsigned long long* xslots, int N, int xwords, hipStream_t stream) {
   const int nvec = V / EPV;
   const int vps = (nvec + splits - 1) / splits;
   const dim3 grid(static_cast<unsigned int>(rows * splits)), block(kRowThreads);
   if (sampling)
     hipLaunchKernelGGL((row_reduce_kernel<T, EPV, true>), grid, block, 0, stream, static_cast<const T*>(logits), V,
-                       splits, vps, c, partials);
+                       splits, vps, c, partials, xslots, N, xwords);
   else
     hipLaunchKernelGGL((row_reduce_kernel<T, EPV, false>), grid, block, 0, stream, static_cast<const T*>(logits), V,
-                       splits, vps, c, partials);
+                       splits, vps, c, partials, xslots, N, xwords);
   return hipGetLastError();
 }
 
 // 16-byte loads need every row to start on a 16-byte boundary; otherwise the same kernel runs
 // with one element per load.
 static hipError_t launch_row_reduce(const void* logits, int dtype, long rows, int V, int splits, bool sampling,
-                                    float c, Partial* partials, hipStream_t stream) {
+                                    float c, Partial* partials, unsigned long long* xslots, int N, int xwords, hipStream_t stream) {
   const size_t elt = dtype == MARS_BF16 ? 2 : 4;
   const bool wide = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && ((static_cast<size_t>(V) * elt) % 16 == 0);
   if (dtype == MARS_BF16)
-    return wide ? launch_row_reduce_t<bf16_t, 8>(logits, rows, V, splits, sampling, c, partials, stream)
-                : launch_row_reduce_t<bf16_t, 1>(logits, rows, V, splits, sampling, c, partials, stream);
-  return wide ? launch_row_reduce_t<float, 4>(logits, rows, V, splits, sampling, c, partials, stream)
-              : launch_row_reduce_t<float, 1>(logits, rows, V, splits, sampling, c, partials, stream);
+    return wide ? launch_row_reduce_t<bf16_t, 8>(logits, rows, V, splits, sampling, c, partials, xslots, N, xwords, stream)
+                : launch_row_reduce_t<bf16_t, 1>(logits, rows, V, splits, sampling, c, partials, xslots, N, xwords, stream);
+  return wide ? launch_row_reduce_t<float, 4>(logits, rows, V, splits, sampling, c, partials, xslots, N, xwords, stream)
+              : launch_row_reduce_t<float, 1>(logits, rows, V, splits, sampling, c, partials, xslots, N, xwords, stream);
 }
 
 static float log2e_over_t(float temperature) {
@@ -115,8 +134,9 @@ int mars_row_reduce(const void* logits, int logits_dtype, float temperature, int
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0 || workspace_bytes < L.total)
     return MARS_ERR_WORKSPACE;
   Partial* partials = reinterpret_cast<Partial*>(static_cast<char*>(workspace) + L.partials_off);
+  unsigned long long* xslots = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + L.xslots_off);
   const hipError_t e = launch_row_reduce(logits, logits_dtype, static_cast<long>(B) * N, V, L.splits,
-                                         temperature > 0.0f, log2e_over_t(temperature), partials,
+                                         temperature > 0.0f, log2e_over_t(temperature), partials, xslots, N, 2 * L.G,
                                          static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? MARS_OK : MARS_ERR_HIP;
 }
@@ -135,8 +155,9 @@ int mars_row_stats(const void* logits, int logits_dtype, const float* theta, flo
   const long rows = static_cast<long>(B) * N;
   Partial* partials = reinterpret_cast<Partial*>(static_cast<char*>(workspace) + L.partials_off);
   const float c = log2e_over_t(temperature);
-  if (launch_row_reduce(logits, logits_dtype, rows, V, L.splits, temperature > 0.0f, c, partials, stream) !=
-      hipSuccess)
+  unsigned long long* xslots = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + L.xslots_off);
+  if (launch_row_reduce(logits, logits_dtype, rows, V, L.splits, temperature > 0.0f, c, partials, xslots, N, 2 * L.G,
+                        stream) != hipSuccess)
     return MARS_ERR_HIP;
   const int threads = 256;
   hipLaunchKernelGGL(merge_stats_kernel, dim3(static_cast<unsigned int>((rows + threads - 1) / threads)),
@@ -169,32 +190,46 @@ int mars_verify(const void* logits, int logits_dtype, const int32_t* draft_token
   Partial* partials = reinterpret_cast<Partial*>(ws + L.partials_off);
   const float c = log2e_over_t(temperature);
 
-  if (launch_row_reduce(logits, logits_dtype, rows, V, L.splits, sampling, c, partials, stream) != hipSuccess)
+  unsigned long long* xslots = reinterpret_cast<unsigned long long*>(ws + L.xslots_off);
+  if (launch_row_reduce(logits, logits_dtype, rows, V, L.splits, sampling, c, partials, xslots, N, 2 * L.G, stream) !=
+      hipSuccess)
     return MARS_ERR_HIP;
 
   TailArgs a;
   a.logits = logits; a.tok = draft_tokens; a.par = tree_parent;
   a.dprobs = dense ? draft_probs : nullptr;
   a.theta = theta; a.u = uniforms; a.partials = partials;
-  a.stats = stats ? stats : reinterpret_cast<mars_row_stat*>(ws + L.stats_off);
+  a.stats = stats;
+  a.stats_ws = reinterpret_cast<mars_row_stat*>(ws + L.stats_off);
+  a.G = sampling ? L.G : 1;
+  a.spin_limit = 1 << 20;  // on the order of a second of polling before a request gives up on its partners
+  a.xslots = xslots;
   a.mask = accept_mask; a.len = accept_len; a.path = path_idx; a.bonus = bonus_token;
   a.dec = decision; a.status = request_status; a.diag = diag;
   a.B = B; a.N = N; a.V = V; a.splits = L.splits; a.c = c;
 
-  const dim3 grid(static_cast<unsigned int>(B));
   if (!sampling) {
-    hipLaunchKernelGGL(tail_greedy_kernel, grid, dim3(kGreedyThreads), 0, stream, a);
-  } else if (logits_dtype == MARS_BF16) {
-    if (dense && draft_dtype == MARS_BF16)
-      hipLaunchKernelGGL((tail_sampling_kernel<bf16_t, bf16_t>), grid, dim3(kSamplingThreads), 0, stream, a);
-    else
-      hipLaunchKernelGGL((tail_sampling_kernel<bf16_t, float>), grid, dim3(kSamplingThreads), 0, stream, a);
-  } else {
-    if (dense && draft_dtype == MARS_BF16)
-      hipLaunchKernelGGL((tail_sampling_kernel<float, bf16_t>), grid, dim3(kSamplingThreads), 0, stream, a);
-    else
-      hipLaunchKernelGGL((tail_sampling_kernel<float, float>), grid, dim3(kSamplingThreads), 0, stream, a);
+    hipLaunchKernelGGL(tail_greedy_kernel, dim3(static_cast<unsigned int>(B)), dim3(kGreedyThreads), 0, stream, a);
+    return hipGetLastError() == hipSuccess ? MARS_OK : MARS_ERR_HIP;
   }
+  const void* kernel;
+  if (logits_dtype == MARS_BF16)
+    kernel = (dense && draft_dtype == MARS_BF16) ? reinterpret_cast<const void*>(&tail_sampling_kernel<bf16_t, bf16_t>)
+                                                 : reinterpret_cast<const void*>(&tail_sampling_kernel<bf16_t, float>);
+  else
+    kernel = (dense && draft_dtype == MARS_BF16) ? reinterpret_cast<const void*>(&tail_sampling_kernel<float, bf16_t>)
+                                                 : reinterpret_cast<const void*>(&tail_sampling_kernel<float, float>);
+  void* params[] = {&a};
+  // With G > 1 the work-groups of a request wait for each other.  The grid never exceeds one
+  // work-group per compute unit, so on a device that is free to run it (the row reduction before
+  // it on the same stream has finished by then) every work-group is resident from the start.
+  // The waits are bounded: should foreign work keep part of the grid from being scheduled, the
+  // affected requests end with MARS_REQ_TIMEOUT instead of hanging.  (A cooperative launch
+  // would have the runtime check residency, at the price of ~20 us per call on this stack.)
+  if (hipLaunchKernel(kernel, dim3(static_cast<unsigned int>(B) * a.G), dim3(kSamplingThreads), params, 0,
+                      stream) !=
+      hipSuccess)
+    return MARS_ERR_HIP;
   return hipGetLastError() == hipSuccess ? MARS_OK : MARS_ERR_HIP;
 }
 

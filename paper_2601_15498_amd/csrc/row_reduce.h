@@ -41,7 +41,8 @@ __device__ void scan_batch(const T* __restrict__ rowp, int v_begin, int v_end, i
 template <typename T, int EPV, bool SAMPLING>
 __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __restrict__ logits, int V, int splits,
                                                                   int vecs_per_split, float c,
-                                                                  Partial* __restrict__ partials) {
+                                                                  Partial* __restrict__ partials,
+                                                                  unsigned long long* __restrict__ xslots, int N, int xwords) {
   constexpr int U = kUnroll;
   constexpr int BV = kRowThreads * U;  // vectors per batch
   constexpr int NE = U * EPV;          // elements per lane per batch
@@ -57,6 +58,18 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   const int tid = threadIdx.x;
   const int nb = (nv + BV - 1) / BV;
   const int nfull = nv / BV;  // batches that need no bounds check
+
+  // Exchange words of the tail kernel that follows on the stream (xwords per (request, exchange),
+  // N + 2 exchanges per request): cleared here so that the call needs no separate memset.
+  if (split == 0 && tid < xwords) {
+    const int b = row / N, i = row - b * N;
+    unsigned long long* cells = xslots + static_cast<size_t>(b) * (N + 2) * xwords;
+    cells[static_cast<size_t>(i) * xwords + tid] = 0ull;
+    if (i == 0) {
+      cells[static_cast<size_t>(N) * xwords + tid] = 0ull;
+      cells[static_cast<size_t>(N + 1) * xwords + tid] = 0ull;
+    }
+  }
 
   float m1 = neg_inf(), m2 = neg_inf();  // best and second-best batch maximum of this lane
   int b1 = -1, b2 = -1;                  // the (distinct) batches they belong to

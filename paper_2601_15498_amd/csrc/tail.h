@@ -14,7 +14,7 @@
 namespace mars {
 
 constexpr int kGreedyThreads = 256;
-constexpr int kSamplingThreads = 1024;
+constexpr int kSamplingThreads = 512;
 constexpr int kMaxTiles = 512;  // CDF tiles kept in LDS for the final draw
 
 struct TailArgs {
@@ -25,7 +25,8 @@ struct TailArgs {
   const float* theta;
   const float* u;
   const Partial* partials;
-  mars_row_stat* stats;  // [B*N], written here (caller's table or workspace)
+  mars_row_stat* stats;     // optional caller's table [B*N]
+  mars_row_stat* stats_ws;  // [B*N] in the workspace: the table the tail itself reads
   uint8_t* mask;
   int32_t* len;
   int32_t* path;
@@ -35,19 +36,27 @@ struct TailArgs {
   mars_req_diag* diag;   // optional
   int B, N, V, splits;
   float c;               // log2(e) / T, 0 in greedy mode
+  // sampling mode: G work-groups share one request and exchange partial sums
+  int G;
+  int spin_limit;        // polls before an exchange gives up
+  unsigned long long* xslots;  // [B][N+2][G][2] tagged exchange words, cleared by the row reduction
 };
 
 // ---------------------------------------------------------------- steps shared by both modes
 // Merge this request's rows, validate tree and tokens.  Returns the request status
 // (uniform over the work-group).  Ends with a barrier: stats of the request are visible.
 template <int NT>
-__device__ int merge_and_validate(const TailArgs& a, int b) {
+__device__ int merge_and_validate(const TailArgs& a, int b, bool write_user_stats) {
   const int N = a.N;
   const float theta = a.theta[b];
   int bad = 0;
   for (int i = threadIdx.x; i < N; i += NT) {
     const size_t r = static_cast<size_t>(b) * N + i;
-    merge_row(a.partials + r * a.splits, a.splits, theta, a.c, &a.stats[r]);
+    mars_row_stat st;
+    merge_row(a.partials + r * a.splits, a.splits, theta, a.c, &st);
+    // Several work-groups of a request may write the workspace copy: they write identical bits.
+    a.stats_ws[r] = st;
+    if (write_user_stats && a.stats) a.stats[r] = st;
     const int p = a.par[r];
     const int t = a.tok[r];
     if (i == 0) { if (p != -1) bad |= 1; }
@@ -73,7 +82,7 @@ __device__ void write_rejected_request(const TailArgs& a, int b, int status) {
   }
   if (threadIdx.x == 0) {
     a.len[b] = 0;
-    a.bonus[b] = a.stats[static_cast<size_t>(b) * N].id1;
+    a.bonus[b] = a.stats_ws[static_cast<size_t>(b) * N].id1;
     if (a.status) a.status[b] = status;
     if (a.diag) { mars_req_diag d = {0.0f, 0.0f, 0, 0}; a.diag[b] = d; }
   }
@@ -91,7 +100,7 @@ __global__ __launch_bounds__(kGreedyThreads) void tail_greedy_kernel(TailArgs a)
   const int b = blockIdx.x;
   const int N = a.N;
   const size_t rb = static_cast<size_t>(b) * N;
-  const int status = merge_and_validate<NT>(a, b);
+  const int status = merge_and_validate<NT>(a, b, true);
   if (status != MARS_REQ_OK) { write_rejected_request<NT>(a, b, status); return; }
 
   // Local decision of every node against its parent's row (Alg. 1 if-chain).
@@ -100,7 +109,7 @@ __global__ __launch_bounds__(kGreedyThreads) void tail_greedy_kernel(TailArgs a)
     if (i > 0) {
       const int p = a.par[rb + i];
       const int t = a.tok[rb + i];
-      const mars_row_stat st = a.stats[rb + p];
+      const mars_row_stat st = a.stats_ws[rb + p];
       if (t == st.id1) code = MARS_DEC_EXACT;
       else if (t == st.id2 && st.relax_ok) code = MARS_DEC_RELAXED;
       anc = p; dep = 1;
@@ -149,7 +158,7 @@ __global__ __launch_bounds__(kGreedyThreads) void tail_greedy_kernel(TailArgs a)
       n = a.par[rb + n];
     }
     a.len[b] = L;
-    a.bonus[b] = a.stats[rb + e].id1;  // correction after a rejection, bonus after a leaf
+    a.bonus[b] = a.stats_ws[rb + e].id1;  // correction after a rejection, bonus after a leaf
     if (a.status) a.status[b] = MARS_REQ_OK;
     if (a.diag) { mars_req_diag dg = {0.0f, 0.0f, 0, e}; a.diag[b] = dg; }
   }
@@ -188,17 +197,30 @@ __device__ __forceinline__ void load8<float>(const float* __restrict__ row, int 
 
 // The residual chain at the current node: rejection j replaced f by
 // max(0, f - q_j) * inv_norm[j] (q_j dense, or one-hot at tok[j]).
+// The first kChainRegs entries live in (wave-uniform) registers, so that the per-element
+// evaluation touches no memory; longer chains continue in LDS.
+constexpr int kChainRegs = 4;
 struct Chain {
   const int32_t* tok;      // LDS
   const float* inv_norm;   // LDS; 0 marks "Z was 0, f left unchanged"
   int n;
+  int rtok[kChainRegs];
+  float rinv[kChainRegs];
 };
 
 // f(v) for the current node: softmax term, then the residual chain.
 __device__ __forceinline__ float eval_f(float z, float q, int v, float z1, float c, float inv_S, bool dense,
                                         const Chain& ch) {
   float f = __builtin_amdgcn_exp2f((z - z1) * c) * inv_S;
-  for (int j = 0; j < ch.n; ++j) {
+#pragma unroll
+  for (int j = 0; j < kChainRegs; ++j) {
+    if (j < ch.n) {
+      const float qj = dense ? q : (v == ch.rtok[j] ? 1.0f : 0.0f);
+      const float g = fmaxf(f - qj, 0.0f);
+      f = ch.rinv[j] > 0.0f ? g * ch.rinv[j] : f;
+    }
+  }
+  for (int j = kChainRegs; j < ch.n; ++j) {
     const float qj = dense ? q : (v == ch.tok[j] ? 1.0f : 0.0f);
     const float g = fmaxf(f - qj, 0.0f);
     const float inv = ch.inv_norm[j];
@@ -219,72 +241,227 @@ __device__ __forceinline__ double block_sum(double v, double* sh) {
   return t;
 }
 
+// Sum of one double per work-group over the G work-groups of a request, in work-group order
+// (so every work-group obtains the same bits).  Exchange number `idx` of request b has its own
+// 2*G words, cleared by the row reduction of the same call.  A work-group publishes its value as
+// two floats (head and tail of the double), each packed with a non-zero tag into one 64-bit
+// word, so that a single store both delivers the data and signals arrival; the partners poll
+// the words directly.  The wait is bounded: if a partner does not arrive within `spin_limit`
+// polls the request is flagged and the kernel carries on to its end with what it has.
+__device__ __forceinline__ unsigned long long pack_tagged(float v) {
+  return (1ull << 32) | static_cast<unsigned long long>(__float_as_uint(v));
+}
+template <int NT>
+__device__ double exchange_sum(const TailArgs& a, int b, int g, int idx, double mine, double* sh_part,
+                               int* sh_flag) {
+  const int G = a.G;
+  if (G == 1) { sh_part[0] = mine; return mine; }
+  unsigned long long* cell = a.xslots + (static_cast<size_t>(b) * (a.N + 2) + idx) * (2 * G);
+  if (threadIdx.x == 0) {
+    const float hi = static_cast<float>(mine);
+    const float lo = static_cast<float>(mine - static_cast<double>(hi));
+    __hip_atomic_store(&cell[2 * g], pack_tagged(hi), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&cell[2 * g + 1], pack_tagged(lo), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (threadIdx.x < G) {
+    double v = 0.0;
+    for (int h = 0; h < 2; ++h) {
+      unsigned long long w = 0;
+      int spins = 0;
+      for (;;) {
+        w = __hip_atomic_load(&cell[2 * threadIdx.x + h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((w >> 32) != 0ull) break;
+        if (++spins > a.spin_limit) { *sh_flag = 1; break; }
+        __builtin_amdgcn_s_sleep(1);
+      }
+      v += static_cast<double>(__uint_as_float(static_cast<unsigned int>(w)));
+    }
+    sh_part[threadIdx.x] = v;
+  }
+  __syncthreads();
+  double t = 0.0;
+  for (int i = 0; i < G; ++i) t += sh_part[i];
+  __syncthreads();  // sh_part may be rewritten by the next exchange
+  return t;
+}
+
+// Everything a pass over a row needs to evaluate the current distribution f.
+template <typename T, typename TQ>
+struct RowView {
+  const T* zrow;
+  const TQ* qrow;   // nullptr = one-hot draft distribution
+  int V;
+  bool vec_ok;
+  float z1, c, inv_S;
+  Chain ch;
+  __device__ __forceinline__ void load(int gi, float (&z)[8], float (&q)[8]) const {
+    load8<T>(zrow, gi, V, vec_ok, neg_inf(), z);
+    if (qrow) load8<TQ>(qrow, gi, V, vec_ok, 0.0f, q);
+  }
+  __device__ __forceinline__ float f(const float (&z)[8], const float (&q)[8], int gi, int e) const {
+    return eval_f(z[e], qrow ? q[e] : 0.0f, gi * 8 + e, z1, c, inv_S, qrow != nullptr, ch);
+  }
+};
+
+constexpr int kPassBatch = 4;  // groups whose loads a thread issues before it starts computing
+
+// This work-group's share of Z = sum_v max(0, f(v) - q_k(v)) over groups [g_begin, g_end):
+// q_k dense, or one-hot at token x.  The loads of kPassBatch groups are issued together so
+// that a pass costs about one memory round trip per batch, not one per group.
+template <typename T, typename TQ, int NT>
+__device__ double residual_mass_slice(const RowView<T, TQ>& rv, int g_begin, int g_end, int x) {
+  double part = 0.0;
+  for (int base = g_begin + static_cast<int>(threadIdx.x); base < g_end; base += kPassBatch * NT) {
+    float z[kPassBatch][8], q[kPassBatch][8];
+#pragma unroll
+    for (int i = 0; i < kPassBatch; ++i) {
+      const int gi = base + i * NT;
+      if (gi < g_end) rv.load(gi, z[i], q[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < kPassBatch; ++i) {
+      const int gi = base + i * NT;
+      if (gi < g_end) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float qk = rv.qrow ? q[i][e] : (gi * 8 + e == x ? 1.0f : 0.0f);
+          acc += fmaxf(rv.f(z[i], q[i], gi, e) - qk, 0.0f);
+        }
+        part += static_cast<double>(acc);
+      }
+    }
+  }
+  return part;
+}
+
+constexpr int kMaxGroupsPerRequest = 32;   // work-groups that may share one request
+constexpr float kClosedFormMinNorm = 0.1f; // one-hot residual: Z = 1 - f(x) is used when at least this
+
 template <typename T, typename TQ>
 __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArgs a) {
   constexpr int NT = kSamplingThreads;
   constexpr int NW = NT / kWave;
-  __shared__ int16_t sh_first[MARS_MAX_NODES];   // first child (-1 none)
-  __shared__ int16_t sh_next[MARS_MAX_NODES];    // next sibling (-1 none)
+  __shared__ int16_t sh_par[MARS_MAX_NODES];     // parent of every node
+  __shared__ int32_t sh_tok[MARS_MAX_NODES];     // draft token of every node
+  __shared__ unsigned long long sh_kids[MARS_MAX_NODES / kWave];  // bit i of word w: node 64w+i is a child of the current node
+  __shared__ float sh_zx[MARS_MAX_NODES];        // logit of the node's token in its parent's row
+  __shared__ float sh_qx[MARS_MAX_NODES];        // draft probability of the node's token (1 if one-hot)
   __shared__ int32_t sh_ctok[MARS_MAX_NODES];    // residual chain: rejected tokens
   __shared__ float sh_cinv[MARS_MAX_NODES];      // residual chain: 1/Z
   __shared__ double sh_red[NW];
+  __shared__ double sh_part[kMaxGroupsPerRequest];
   __shared__ double sh_tile[kMaxTiles];
   __shared__ int sh_accept;                      // decision code of the child under test
+  __shared__ float sh_fx;                        // f(x) of the child under test
+  __shared__ int sh_flag;                        // exchange timed out
+  __shared__ int sh_bad;                         // validation bits of the request
 
-  const int b = blockIdx.x;
+  const int G = a.G;
+  const int b = blockIdx.x / G, g = blockIdx.x - b * G;
   const int N = a.N, V = a.V;
   const size_t rb = static_cast<size_t>(b) * N;
   const int tid = threadIdx.x;
-  const int status = merge_and_validate<NT>(a, b);
-  if (status != MARS_REQ_OK) { write_rejected_request<NT>(a, b, status); return; }
-
-  // Child lists in increasing node index.
-  for (int i = tid; i < N; i += NT) {
-    int fc = -1, ns = -1;
-    for (int j = i + 1; j < N; ++j)
-      if (a.par[rb + j] == i) { fc = j; break; }
-    if (i > 0) {
-      const int p = a.par[rb + i];
-      for (int j = i + 1; j < N; ++j)
-        if (a.par[rb + j] == p) { ns = j; break; }
-    }
-    sh_first[i] = static_cast<int16_t>(fc);
-    sh_next[i] = static_cast<int16_t>(ns);
-    a.mask[rb + i] = i == 0 ? 1 : 0;
-    a.path[rb + i] = -1;
-    if (a.dec) a.dec[rb + i] = 0;
-  }
+  if (tid == 0) { sh_flag = 0; sh_bad = 0; }
   __syncthreads();
 
   const T* __restrict__ zall = static_cast<const T*>(a.logits) + rb * static_cast<size_t>(V);
   const TQ* __restrict__ qall = a.dprobs ? static_cast<const TQ*>(a.dprobs) + rb * static_cast<size_t>(V) : nullptr;
   const bool dense = qall != nullptr;
+
+  // Prologue, one node per thread: validate tree and token, start the two gathers every
+  // acceptance test needs (logit and draft probability of the node's token in its parent's
+  // row: one round trip for the whole tree instead of one per visited node), and merge the
+  // row partials while those loads are in flight.  Every work-group of the request does this
+  // for itself; they produce identical bits, and only the first writes the caller's outputs.
+  {
+    const float theta = a.theta[b];
+    for (int i = tid; i < N; i += NT) {
+      const size_t r = rb + i;
+      const int p = a.par[r];
+      const int x = a.tok[r];
+      int bad = 0;
+      if (i == 0) { if (p != -1) bad = 1; }
+      else {
+        if (p < 0 || p >= i) bad |= 1;
+        if (x < 0 || x >= V) bad |= 2;
+      }
+      const size_t at = (i > 0 && bad == 0) ? static_cast<size_t>(p) * V + x : 0;
+      const float zx = widen(zall[at]);
+      const float qx = dense ? widen(qall[at]) : 1.0f;
+      mars_row_stat st;
+      merge_row(a.partials + r * a.splits, a.splits, theta, a.c, &st);
+      a.stats_ws[r] = st;
+      if (g == 0 && a.stats) a.stats[r] = st;
+      sh_par[i] = static_cast<int16_t>(p);
+      sh_tok[i] = x;
+      sh_zx[i] = zx;
+      sh_qx[i] = qx;
+      if (bad) atomicOr(&sh_bad, bad);
+      if (g == 0) {
+        a.mask[r] = i == 0 ? 1 : 0;
+        a.path[r] = -1;
+        if (a.dec) a.dec[r] = 0;
+      }
+    }
+  }
+  __syncthreads();
+  if (sh_bad != 0) {
+    if (g == 0) write_rejected_request<NT>(a, b, (sh_bad & 1) ? MARS_REQ_BAD_TREE : MARS_REQ_BAD_TOKEN);
+    return;
+  }
+  const mars_row_stat* __restrict__ stats = a.stats_ws + rb;
+  const int nwords = (N + kWave - 1) / kWave;
+
   const bool vec_ok = (V % 8 == 0) && (reinterpret_cast<uintptr_t>(zall) % 16 == 0) &&
                       (!dense || reinterpret_cast<uintptr_t>(qall) % 16 == 0);
   const int ngroups = (V + 7) / 8;
+  // This work-group's slice of the vocabulary, in groups of eight elements (a multiple of 64
+  // groups, so that the slices are made of whole wave steps).
+  const int slice = ((ngroups + G - 1) / G + kWave - 1) / kWave * kWave;
+  const int g_begin = min(ngroups, g * slice), g_end = min(ngroups, g_begin + slice);
   const float c = a.c;
   const float* __restrict__ u = a.u + static_cast<size_t>(b) * (N + 1);
 
-  int cnode = 0, plen = 0, passes = 0;
+  int cnode = 0, plen = 0, passes = 0, nexch = 0;
   float last_norm = 0.0f;
-  Chain ch = {sh_ctok, sh_cinv, 0};
+  bool pending_norm = false;  // the last rejection's normaliser is still to come out of the final pass
+  RowView<T, TQ> rv;
+  rv.V = V; rv.vec_ok = vec_ok; rv.c = c;
+  rv.ch.tok = sh_ctok; rv.ch.inv_norm = sh_cinv; rv.ch.n = 0;
   for (;;) {
-    const mars_row_stat st = a.stats[rb + cnode];
-    const float inv_S = 1.0f / st.sum_exp;
-    const T* __restrict__ zrow = zall + static_cast<size_t>(cnode) * V;
-    const TQ* __restrict__ qrow = dense ? qall + static_cast<size_t>(cnode) * V : nullptr;
-    ch.n = 0;
-    int k = sh_first[cnode];
+    const mars_row_stat st = stats[cnode];
+    rv.zrow = zall + static_cast<size_t>(cnode) * V;
+    rv.qrow = dense ? qall + static_cast<size_t>(cnode) * V : nullptr;
+    rv.z1 = st.z1; rv.inv_S = 1.0f / st.sum_exp;
+    rv.ch.n = 0;
+    pending_norm = false;
+    // children of cnode, as bit masks over the nodes (increasing node index = increasing bit)
+    for (int wd = tid / kWave; wd < nwords; wd += NW) {
+      const int i = wd * kWave + tid % kWave;
+      const unsigned long long m = __ballot(i < N && i > cnode && sh_par[i] == cnode);
+      if (tid % kWave == 0) sh_kids[wd] = m;
+    }
+    __syncthreads();
     int accepted = -1;
-    while (k >= 0) {
-      const int x = a.tok[rb + k];
+    int wd = cnode / kWave;              // children have larger indices than their parent
+    unsigned long long bits = sh_kids[wd];
+    for (;;) {
+      while (bits == 0ull && wd + 1 < nwords) bits = sh_kids[++wd];
+      if (bits == 0ull) break;
+      const int k = wd * kWave + __ffsll(static_cast<long long>(bits)) - 1;
+      bits &= bits - 1;
+      bool more = bits != 0ull;          // does cnode have further children after k?
+      for (int w2 = wd + 1; w2 < nwords && !more; ++w2) more = sh_kids[w2] != 0ull;
+      const int x = sh_tok[k];
       if (tid == 0) {
         int code = 0;
+        float fx = 0.0f;
         if (x == st.id2 && st.relax_ok) {
           code = MARS_DEC_RELAXED;  // runner-up in a low-margin row: accepted outright
         } else {
-          const float qx = dense ? widen(qrow[x]) : 1.0f;
-          const float fx = eval_f(widen(zrow[x]), qx, x, st.z1, c, inv_S, dense, ch);
+          const float qx = sh_qx[k];
+          fx = eval_f(sh_zx[k], qx, x, st.z1, c, rv.inv_S, dense, rv.ch);
           // Eq. 1: accept with probability min(1, f(x)/q(x))
           float acc;
           if (fx == 0.0f) acc = 0.0f;
@@ -293,12 +470,14 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
           if (u[k] < acc) code = MARS_DEC_SAMPLED;
         }
         sh_accept = code;
+        sh_fx = fx;
       }
       __syncthreads();
       const int code = sh_accept;
+      const float fx = sh_fx;
       __syncthreads();  // everyone has read the decision before thread 0 may overwrite it
       if (code) {
-        if (tid == 0) {
+        if (tid == 0 && g == 0) {
           a.mask[rb + k] = 1;
           a.path[rb + plen] = k;
           if (a.dec) a.dec[rb + k] = static_cast<uint8_t>(code);
@@ -306,32 +485,33 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
         accepted = k;
         break;
       }
-      // Rejected: Z = sum_v max(0, f(v) - q_k(v)) over the whole row, f the current distribution.
-      double part = 0.0;
-      for (int g = tid; g < ngroups; g += NT) {
-        float z[8], q[8];
-        load8<T>(zrow, g, V, vec_ok, neg_inf(), z);
-        if (dense) load8<TQ>(qrow, g, V, vec_ok, 0.0f, q);
-        float acc = 0.0f;
+      // Rejected: f <- max(0, f - q_k) / Z with Z = sum_v max(0, f(v) - q_k(v)).
+      //  * With a one-hot q_k only the entry x changes and Z = 1 - f(x); that form is used while
+      //    it is well conditioned.
+      //  * After the node's last child nothing is tested against f any more: the division is
+      //    left out (factor 1) and Z comes out of the final pass as the total of what is left.
+      //  * Otherwise Z is summed over the row, every work-group of the request taking a slice.
+      float inv;
+      if (!dense && 1.0f - fx >= kClosedFormMinNorm) {
+        last_norm = 1.0f - fx;
+        inv = 1.0f / last_norm;
+      } else if (!more) {
+        pending_norm = true;
+        inv = 1.0f;
+      } else {
+        double part = residual_mass_slice<T, TQ, NT>(rv, g_begin, g_end, x);
+        part = block_sum<NT>(part, sh_red);
+        const double Z = exchange_sum<NT>(a, b, g, nexch++, part, sh_part, &sh_flag);
+        last_norm = static_cast<float>(Z);
+        inv = Z > 0.0 ? static_cast<float>(1.0 / Z) : 0.0f;  // 0: f is left as it is
+      }
+      if (tid == 0) { sh_ctok[rv.ch.n] = x; sh_cinv[rv.ch.n] = inv; }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int v = g * 8 + e;
-          const float f = eval_f(z[e], dense ? q[e] : 0.0f, v, st.z1, c, inv_S, dense, ch);
-          const float qk = dense ? q[e] : (v == x ? 1.0f : 0.0f);
-          acc += fmaxf(f - qk, 0.0f);
-        }
-        part += static_cast<double>(acc);
-      }
-      const double Z = block_sum<NT>(part, sh_red);
-      if (tid == 0) {
-        sh_ctok[ch.n] = x;
-        sh_cinv[ch.n] = Z > 0.0 ? static_cast<float>(1.0 / Z) : 0.0f;
-      }
-      ch.n += 1;
+      for (int j = 0; j < kChainRegs; ++j)
+        if (j == rv.ch.n) { rv.ch.rtok[j] = x; rv.ch.rinv[j] = inv; }
+      rv.ch.n += 1;
       passes += 1;
-      last_norm = static_cast<float>(Z);
       __syncthreads();
-      k = sh_next[k];
     }
     if (accepted < 0) break;
     cnode = accepted;
@@ -339,159 +519,184 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   }
 
   // ---------------------------------------------------------------- inverse-CDF draw from f at cnode
-  const mars_row_stat st = a.stats[rb + cnode];
-  const float inv_S = 1.0f / st.sum_exp;
-  const T* __restrict__ zrow = zall + static_cast<size_t>(cnode) * V;
-  const TQ* __restrict__ qrow = dense ? qall + static_cast<size_t>(cnode) * V : nullptr;
-  // Wave w owns a contiguous run of groups; a tile is `rep` consecutive 64-group steps of a wave.
-  const int steps_total = (ngroups + kWave - 1) / kWave;
+  const mars_row_stat st = stats[cnode];
+  // Inside the slice, wave w owns a contiguous run of 64-group steps; a tile is `rep`
+  // consecutive steps of one wave.
+  const int steps_total = (g_end - g_begin + kWave - 1) / kWave;
   const int steps_per_wave = (steps_total + NW - 1) / NW;
-  const int rep = (steps_per_wave * NW + kMaxTiles - 1) / kMaxTiles;
+  const int rep = max(1, (steps_per_wave * NW + kMaxTiles - 1) / kMaxTiles);
   const int tiles_per_wave = (steps_per_wave + rep - 1) / rep;
   const int ntiles = tiles_per_wave * NW;
   const int wave = tid / kWave, lane = tid % kWave;
 
-  auto group_values = [&](int g, float (&f)[8]) {
-    float z[8], q[8];
-    load8<T>(zrow, g, V, vec_ok, neg_inf(), z);
-    if (dense) load8<TQ>(qrow, g, V, vec_ok, 0.0f, q);
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      f[e] = eval_f(z[e], dense ? q[e] : 0.0f, g * 8 + e, st.z1, c, inv_S, dense, ch);
+  auto step_group = [&](int w, int sw) {  // group of this lane in step sw of wave w, -1 = nothing there
+    const int gi = g_begin + (w * steps_per_wave + sw) * kWave + lane;
+    return (sw < steps_per_wave && gi < g_end) ? gi : -1;
   };
-  auto tile_step_group = [&](int tile, int r) {  // group handled by this lane in step r of a tile
-    const int w = tile / tiles_per_wave, t = tile % tiles_per_wave;
-    const int step = w * steps_per_wave + t * rep + r;
-    const bool in_wave = (t * rep + r) < steps_per_wave;
-    return in_wave ? step * kWave + lane : ngroups;  // ngroups = out of range
+  auto group_sum = [&](const float (&z)[8], const float (&q)[8], int gi, float (&f)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = rv.f(z, q, gi, e);
+    return ((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7]));
   };
 
-  for (int t = 0; t < tiles_per_wave; ++t) {
-    const int tile = wave * tiles_per_wave + t;
+  double total = 0.0, before = 0.0;
+  int owner = 0;
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    // tile sums of this work-group's slice, kPassBatch steps of loads in flight at a time
     double acc = 0.0;
-    for (int r = 0; r < rep; ++r) {
-      const int g = tile_step_group(tile, r);
-      if (g < ngroups) {
-        float f[8];
-        group_values(g, f);
-        acc += static_cast<double>(((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7])));
+    for (int s0 = 0; s0 < steps_per_wave; s0 += kPassBatch) {
+      float z[kPassBatch][8], q[kPassBatch][8];
+#pragma unroll
+      for (int i = 0; i < kPassBatch; ++i) {
+        const int gi = step_group(wave, s0 + i);
+        if (gi >= 0) rv.load(gi, z[i], q[i]);
+      }
+#pragma unroll
+      for (int i = 0; i < kPassBatch; ++i) {
+        const int sw = s0 + i;
+        if (sw < steps_per_wave) {
+          const int gi = step_group(wave, sw);
+          if (gi >= 0) { float f[8]; acc += static_cast<double>(group_sum(z[i], q[i], gi, f)); }
+          if ((sw + 1) % rep == 0 || sw + 1 == steps_per_wave) {
+            const double t = wave_sum(acc);
+            if (lane == 0) sh_tile[wave * tiles_per_wave + sw / rep] = t;
+            acc = 0.0;
+          }
+        }
       }
     }
-    acc = wave_sum(acc);
-    if (lane == 0) sh_tile[tile] = acc;
-  }
-  __syncthreads();
-  // Wave 0: prefix over the tiles in index order, locate the tile, then the element.
-  if (wave == 0) {
-    const int per_lane = (ntiles + kWave - 1) / kWave;
-    double mine = 0.0;
-    for (int i = 0; i < per_lane; ++i) {
-      const int t = lane * per_lane + i;
-      if (t < ntiles) mine += sh_tile[t];
-    }
-    double incl = mine;  // inclusive scan over lanes
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-      const double o = __shfl_up(incl, d, kWave);
-      if (lane >= d) incl += o;
-    }
-    const double total = __shfl(incl, kWave - 1, kWave);
+    __syncthreads();
+    // slice total = sum of its tiles in index order (the same additions the search below repeats)
+    double wg_total = 0.0;
+    for (int t = 0; t < ntiles; ++t) wg_total += sh_tile[t];
+    total = exchange_sum<NT>(a, b, g, N + attempt, wg_total, sh_part, &sh_flag);
+    // Which work-group's slice holds the target?  The last one with mass if rounding leaves none.
     const double target = static_cast<double>(u[N]) * total;
-    // first lane whose inclusive prefix exceeds the target
-    const unsigned long long over = __ballot(incl > target);
-    int pick = -1;
-    float pick_f = 0.0f;
-    if (total > 0.0 && over != 0ull) {
-      const int L = __ffsll(static_cast<long long>(over)) - 1;
-      const double before_lane = __shfl(incl - mine, L, kWave);
-      // tiles of lane L in order
-      double cum = before_lane;
-      int tile = -1;
-      for (int i = 0; i < per_lane; ++i) {
-        const int t = L * per_lane + i;
-        if (t >= ntiles) break;
-        const double nxt = cum + sh_tile[t];
-        if (nxt > target) { tile = t; break; }
-        cum = nxt;
+    before = 0.0;
+    owner = -1;
+    int last_mass = -1;
+    for (int i = 0; i < G; ++i) {
+      if (sh_part[i] > 0.0) last_mass = i;
+      if (owner < 0) {
+        if (before + sh_part[i] > target) owner = i; else before += sh_part[i];
       }
-      if (tile < 0) tile = min(ntiles - 1, L * per_lane + per_lane - 1);
-      // walk the tile step by step; cum is the mass before the current step
-      int last_pos_v = -1;
-      float last_pos_f = 0.0f;
-      for (int r = 0; r < rep && pick < 0; ++r) {
-        const int g = tile_step_group(tile, r);
-        float f[8];
-        float gs = 0.0f;
-        if (g < ngroups) {
-          group_values(g, f);
-          gs = ((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7]));
-        } else {
+    }
+    if (owner < 0) {
+      owner = last_mass < 0 ? 0 : last_mass;
+      before = 0.0;
+      for (int i = 0; i < owner; ++i) before += sh_part[i];
+    }
+    __syncthreads();
+    if (!(pending_norm && total <= 0.0)) break;
+    // The postponed normaliser turned out to be 0: that rejection leaves f as it was
+    // (cannot happen in exact arithmetic).  Drop it from the chain and draw again.
+    if (tid == 0) sh_cinv[rv.ch.n - 1] = 0.0f;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) f[e] = 0.0f;
-        }
-        double gincl = static_cast<double>(gs);
+    for (int j = 0; j < kChainRegs; ++j)
+      if (j == rv.ch.n - 1) rv.ch.rinv[j] = 0.0f;
+    pending_norm = false;
+    last_norm = 0.0f;
+    __syncthreads();
+  }
+  if (pending_norm) last_norm = static_cast<float>(total);
+  const double target = static_cast<double>(u[N]) * total;
+  if (g == 0 && tid == 0) {
+    a.len[b] = plen;
+    if (a.status) a.status[b] = sh_flag ? MARS_REQ_TIMEOUT : MARS_REQ_OK;
+  }
+  if (g != owner || wave != 0) return;
+
+  // Wave 0 of the owning work-group: locate the tile, then the element.
+  int pick = -1;
+  float pick_f = 0.0f;
+  if (total > 0.0) {
+    double cum = before;
+    int tile = -1, last_tile = -1;
+    for (int t = 0; t < ntiles; ++t) {
+      if (sh_tile[t] > 0.0) last_tile = t;
+      if (tile < 0) {
+        if (cum + sh_tile[t] > target) tile = t; else cum += sh_tile[t];
+      }
+    }
+    if (tile < 0) {  // rounding: fall back to the last tile with mass
+      tile = last_tile < 0 ? 0 : last_tile;
+      cum = before;
+      for (int t = 0; t < tile; ++t) cum += sh_tile[t];
+    }
+    const int tw = tile / tiles_per_wave, ts = (tile % tiles_per_wave) * rep;
+    int last_pos_v = -1;
+    float last_pos_f = 0.0f;
+    for (int r = 0; r < rep && pick < 0; ++r) {
+      const int gi = step_group(tw, ts + r);
+      float f[8];
+      float gs = 0.0f;
+      if (gi >= 0) {
+        float z[8], q[8];
+        rv.load(gi, z, q);
+        gs = group_sum(z, q, gi, f);
+      } else {
 #pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-          const double o = __shfl_up(gincl, d, kWave);
-          if (lane >= d) gincl += o;
-        }
-        const unsigned long long hit = __ballot(cum + gincl > target);
-        // remember the last element with mass, in case rounding leaves no step above the target
-        int my_last = -1;
+        for (int e = 0; e < 8; ++e) f[e] = 0.0f;
+      }
+      double gincl = static_cast<double>(gs);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) if (f[e] > 0.0f) my_last = e;
-        const unsigned long long has = __ballot(my_last >= 0);
-        if (has != 0ull) {
-          const int hl = 63 - __clzll(static_cast<long long>(has));
-          const int le = __shfl(my_last, hl, kWave);
-          float fv = 0.0f;
+      for (int d = 1; d < kWave; d <<= 1) {
+        const double o = __shfl_up(gincl, d, kWave);
+        if (lane >= d) gincl += o;
+      }
+      const unsigned long long hit = __ballot(cum + gincl > target);
+      // remember the last element with mass, in case rounding leaves no step above the target
+      int my_last = -1;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) if (e == my_last) fv = f[e];
-          last_pos_f = __shfl(fv, hl, kWave);
-          last_pos_v = __shfl(g, hl, kWave) * 8 + le;
-        }
-        if (hit != 0ull) {
-          const int hl = __ffsll(static_cast<long long>(hit)) - 1;
-          double run = cum + __shfl(gincl - static_cast<double>(gs), hl, kWave);
-          // lane hl scans its eight elements
-          int pe = -1;
-          float pf = 0.0f;
-          if (lane == hl) {
+      for (int e = 0; e < 8; ++e) if (f[e] > 0.0f) my_last = e;
+      const unsigned long long has = __ballot(my_last >= 0);
+      if (has != 0ull) {
+        const int hl = 63 - __clzll(static_cast<long long>(has));
+        const int le = __shfl(my_last, hl, kWave);
+        float fv = 0.0f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-              if (pe < 0) {
-                run += static_cast<double>(f[e]);
-                if (run > target) { pe = e; pf = f[e]; }
-              }
+        for (int e = 0; e < 8; ++e) if (e == my_last) fv = f[e];
+        last_pos_f = __shfl(fv, hl, kWave);
+        last_pos_v = __shfl(gi, hl, kWave) * 8 + le;
+      }
+      if (hit != 0ull) {
+        const int hl = __ffsll(static_cast<long long>(hit)) - 1;
+        double run = cum + __shfl(gincl - static_cast<double>(gs), hl, kWave);
+        int pe = -1;
+        float pf = 0.0f;
+        if (lane == hl) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            if (pe < 0) {
+              run += static_cast<double>(f[e]);
+              if (run > target) { pe = e; pf = f[e]; }
             }
           }
-          pe = __shfl(pe, hl, kWave);
-          if (pe >= 0) {
-            pick_f = __shfl(pf, hl, kWave);
-            pick = __shfl(g, hl, kWave) * 8 + pe;
-          } else {  // rounding left no step above the target inside the lane: last element with mass
-            pick = last_pos_v; pick_f = last_pos_f;
-            break;
-          }
-        } else {
-          cum += __shfl(gincl, kWave - 1, kWave);
         }
+        pe = __shfl(pe, hl, kWave);
+        if (pe >= 0) {
+          pick_f = __shfl(pf, hl, kWave);
+          pick = __shfl(gi, hl, kWave) * 8 + pe;
+        } else {  // rounding left no step above the target inside the lane: last element with mass
+          pick = last_pos_v; pick_f = last_pos_f;
+          break;
+        }
+      } else {
+        cum += __shfl(gincl, kWave - 1, kWave);
       }
-      if (pick < 0) { pick = last_pos_v; pick_f = last_pos_f; }
     }
-    if (pick < 0) { pick = st.id1; pick_f = 0.0f; }  // degenerate: no mass anywhere
-    if (lane == 0) {
-      a.len[b] = plen;
-      a.bonus[b] = pick;
-      if (a.status) a.status[b] = MARS_REQ_OK;
-      if (a.diag) {
-        mars_req_diag dg;
-        dg.bonus_prob = total > 0.0 ? static_cast<float>(static_cast<double>(pick_f) / total) : 0.0f;
-        dg.last_residual_norm = last_norm;
-        dg.residual_passes = passes;
-        dg.last_node = cnode;
-        a.diag[b] = dg;
-      }
+    if (pick < 0) { pick = last_pos_v; pick_f = last_pos_f; }
+  }
+  if (pick < 0) { pick = st.id1; pick_f = 0.0f; }  // degenerate: no mass anywhere
+  if (lane == 0) {
+    a.bonus[b] = pick;
+    if (a.diag) {
+      mars_req_diag dg;
+      dg.bonus_prob = total > 0.0 ? static_cast<float>(static_cast<double>(pick_f) / total) : 0.0f;
+      dg.last_residual_norm = last_norm;
+      dg.residual_passes = passes;
+      dg.last_node = cnode;
+      a.diag[b] = dg;
     }
   }
 }
