@@ -212,13 +212,17 @@ int mars_verify(const void* logits, int logits_dtype, const int32_t* draft_token
     hipLaunchKernelGGL(tail_greedy_kernel, dim3(static_cast<unsigned int>(B)), dim3(kGreedyThreads), 0, stream, a);
     return hipGetLastError() == hipSuccess ? MARS_OK : MARS_ERR_HIP;
   }
+  // Slices of at most kResident groups of eight per thread stay in registers between passes.
+  const int ngroups8 = (V + 7) / 8;
+  const int slice8 = ((ngroups8 + a.G - 1) / a.G + kWave - 1) / kWave * kWave;
+  const bool resident = slice8 <= kResident * kSamplingThreads;
+  const bool qbf = dense && draft_dtype == MARS_BF16;
   const void* kernel;
-  if (logits_dtype == MARS_BF16)
-    kernel = (dense && draft_dtype == MARS_BF16) ? reinterpret_cast<const void*>(&tail_sampling_kernel<bf16_t, bf16_t>)
-                                                 : reinterpret_cast<const void*>(&tail_sampling_kernel<bf16_t, float>);
-  else
-    kernel = (dense && draft_dtype == MARS_BF16) ? reinterpret_cast<const void*>(&tail_sampling_kernel<float, bf16_t>)
-                                                 : reinterpret_cast<const void*>(&tail_sampling_kernel<float, float>);
+#define MARS_PICK(TT, QQ) (resident ? reinterpret_cast<const void*>(&tail_sampling_kernel<TT, QQ, true>) \
+                                    : reinterpret_cast<const void*>(&tail_sampling_kernel<TT, QQ, false>))
+  if (logits_dtype == MARS_BF16) kernel = qbf ? MARS_PICK(bf16_t, bf16_t) : MARS_PICK(bf16_t, float);
+  else kernel = qbf ? MARS_PICK(float, bf16_t) : MARS_PICK(float, float);
+#undef MARS_PICK
   void* params[] = {&a};
   // With G > 1 the work-groups of a request wait for each other.  The grid never exceeds one
   // work-group per compute unit, so on a device that is free to run it (the row reduction before

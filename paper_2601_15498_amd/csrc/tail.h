@@ -337,8 +337,10 @@ __device__ double residual_mass_slice(const RowView<T, TQ>& rv, int g_begin, int
 
 constexpr int kMaxGroupsPerRequest = 32;   // work-groups that may share one request
 constexpr float kClosedFormMinNorm = 0.1f; // one-hot residual: Z = 1 - f(x) is used when at least this
+constexpr int kResident = 4;               // groups of eight elements a thread can keep in registers
 
-template <typename T, typename TQ>
+// RESIDENT: every slice is at most kResident groups per thread (decided by the host from G and V).
+template <typename T, typename TQ, bool RESIDENT>
 __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArgs a) {
   constexpr int NT = kSamplingThreads;
   constexpr int NW = NT / kWave;
@@ -349,6 +351,7 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   __shared__ float sh_qx[MARS_MAX_NODES];        // draft probability of the node's token (1 if one-hot)
   __shared__ int32_t sh_ctok[MARS_MAX_NODES];    // residual chain: rejected tokens
   __shared__ float sh_cinv[MARS_MAX_NODES];      // residual chain: 1/Z
+  __shared__ mars_row_stat sh_st[MARS_MAX_NODES];  // merged row statistics of the request
   __shared__ double sh_red[NW];
   __shared__ double sh_part[kMaxGroupsPerRequest];
   __shared__ double sh_tile[kMaxTiles];
@@ -362,6 +365,7 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   const int N = a.N, V = a.V;
   const size_t rb = static_cast<size_t>(b) * N;
   const int tid = threadIdx.x;
+  const int wave = tid / kWave, lane = tid % kWave;
   if (tid == 0) { sh_flag = 0; sh_bad = 0; }
   __syncthreads();
 
@@ -391,18 +395,19 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
       const float qx = dense ? widen(qall[at]) : 1.0f;
       mars_row_stat st;
       merge_row(a.partials + r * a.splits, a.splits, theta, a.c, &st);
-      a.stats_ws[r] = st;
-      if (g == 0 && a.stats) a.stats[r] = st;
+      sh_st[i] = st;
+      if (g == 0) {
+        a.stats_ws[r] = st;
+        if (a.stats) a.stats[r] = st;
+        a.mask[r] = i == 0 ? 1 : 0;
+        a.path[r] = -1;
+        if (a.dec) a.dec[r] = 0;
+      }
       sh_par[i] = static_cast<int16_t>(p);
       sh_tok[i] = x;
       sh_zx[i] = zx;
       sh_qx[i] = qx;
       if (bad) atomicOr(&sh_bad, bad);
-      if (g == 0) {
-        a.mask[r] = i == 0 ? 1 : 0;
-        a.path[r] = -1;
-        if (a.dec) a.dec[r] = 0;
-      }
     }
   }
   __syncthreads();
@@ -410,7 +415,6 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
     if (g == 0) write_rejected_request<NT>(a, b, (sh_bad & 1) ? MARS_REQ_BAD_TREE : MARS_REQ_BAD_TOKEN);
     return;
   }
-  const mars_row_stat* __restrict__ stats = a.stats_ws + rb;
   const int nwords = (N + kWave - 1) / kWave;
 
   const bool vec_ok = (V % 8 == 0) && (reinterpret_cast<uintptr_t>(zall) % 16 == 0) &&
@@ -420,6 +424,12 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   // groups, so that the slices are made of whole wave steps).
   const int slice = ((ngroups + G - 1) / G + kWave - 1) / kWave * kWave;
   const int g_begin = min(ngroups, g * slice), g_end = min(ngroups, g_begin + slice);
+  // A slice of at most kResident groups per thread stays in registers between the passes over
+  // one node: f is then loaded and exponentiated once per visited node, every further
+  // rejection at that node only updates it in place, and the final draw reads it where it is.
+  // Thread t holds groups g_begin + i*NT + t; "step" s = i*NW + wave is 64 consecutive groups.
+  constexpr bool resident = RESIDENT;
+  const int nsteps = (g_end - g_begin + kWave - 1) / kWave;
   const float c = a.c;
   const float* __restrict__ u = a.u + static_cast<size_t>(b) * (N + 1);
 
@@ -429,18 +439,70 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   RowView<T, TQ> rv;
   rv.V = V; rv.vec_ok = vec_ok; rv.c = c;
   rv.ch.tok = sh_ctok; rv.ch.inv_norm = sh_cinv; rv.ch.n = 0;
+  float fc[kResident][8], qv[kResident][8];  // resident slice: current f and the draft probabilities
+  bool have = false;                          // fc / qv hold this node's slice
+  int applied = 0;                            // chain entries already worked into fc
+
+  // Bring the resident slice up to date with the chain (loading it on first use).
+  auto refresh_resident = [&]() {
+    if (!have) {
+#pragma unroll
+      for (int i = 0; i < kResident; ++i) {
+        const int gi = g_begin + i * NT + tid;
+        if (gi < g_end) {
+          rv.load(gi, fc[i], qv[i]);
+        } else {  // nothing there: f = 0 and q = 0 contribute nothing
+#pragma unroll
+          for (int e = 0; e < 8; ++e) { fc[i][e] = neg_inf(); qv[i][e] = 0.0f; }
+        }
+        if (!dense) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) qv[i][e] = 0.0f;
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < kResident; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          fc[i][e] = __builtin_amdgcn_exp2f((fc[i][e] - rv.z1) * c) * rv.inv_S;  // softmax term (Eq. 3)
+      have = true;
+      applied = 0;
+    }
+    for (int j = applied; j < rv.ch.n; ++j) {
+      int tj = sh_ctok[j];
+      float inv = sh_cinv[j];
+#pragma unroll
+      for (int r = 0; r < kChainRegs; ++r)
+        if (r == j) { tj = rv.ch.rtok[r]; inv = rv.ch.rinv[r]; }
+      if (inv > 0.0f) {
+#pragma unroll
+        for (int i = 0; i < kResident; ++i) {
+          const int gi = g_begin + i * NT + tid;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float qj = dense ? qv[i][e] : (gi * 8 + e == tj ? 1.0f : 0.0f);
+            fc[i][e] = fmaxf(fc[i][e] - qj, 0.0f) * inv;
+          }
+        }
+      }
+    }
+    applied = rv.ch.n;
+  };
+
   for (;;) {
-    const mars_row_stat st = stats[cnode];
+    const mars_row_stat st = sh_st[cnode];
     rv.zrow = zall + static_cast<size_t>(cnode) * V;
     rv.qrow = dense ? qall + static_cast<size_t>(cnode) * V : nullptr;
     rv.z1 = st.z1; rv.inv_S = 1.0f / st.sum_exp;
     rv.ch.n = 0;
     pending_norm = false;
+    have = false;
+    applied = 0;
     // children of cnode, as bit masks over the nodes (increasing node index = increasing bit)
-    for (int wd = tid / kWave; wd < nwords; wd += NW) {
-      const int i = wd * kWave + tid % kWave;
+    for (int wd = wave; wd < nwords; wd += NW) {
+      const int i = wd * kWave + lane;
       const unsigned long long m = __ballot(i < N && i > cnode && sh_par[i] == cnode);
-      if (tid % kWave == 0) sh_kids[wd] = m;
+      if (lane == 0) sh_kids[wd] = m;
     }
     __syncthreads();
     int accepted = -1;
@@ -499,7 +561,23 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
         pending_norm = true;
         inv = 1.0f;
       } else {
-        double part = residual_mass_slice<T, TQ, NT>(rv, g_begin, g_end, x);
+        double part = 0.0;
+        if (resident) {
+          refresh_resident();
+#pragma unroll
+          for (int i = 0; i < kResident; ++i) {
+            const int gi = g_begin + i * NT + tid;
+            float acc = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const float qk = dense ? qv[i][e] : (gi * 8 + e == x ? 1.0f : 0.0f);
+              acc += fmaxf(fc[i][e] - qk, 0.0f);
+            }
+            part += static_cast<double>(acc);
+          }
+        } else {
+          part = residual_mass_slice<T, TQ, NT>(rv, g_begin, g_end, x);
+        }
         part = block_sum<NT>(part, sh_red);
         const double Z = exchange_sum<NT>(a, b, g, nexch++, part, sh_part, &sh_flag);
         last_norm = static_cast<float>(Z);
@@ -519,17 +597,15 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   }
 
   // ---------------------------------------------------------------- inverse-CDF draw from f at cnode
-  const mars_row_stat st = stats[cnode];
-  // Inside the slice, wave w owns a contiguous run of 64-group steps; a tile is `rep`
-  // consecutive steps of one wave.
-  const int steps_total = (g_end - g_begin + kWave - 1) / kWave;
-  const int steps_per_wave = (steps_total + NW - 1) / NW;
+  const mars_row_stat st = sh_st[cnode];
+  // Tiles of the slice, in vocabulary order.  Resident slice: a tile is one step (64 groups).
+  // Otherwise wave w owns a contiguous run of steps and a tile is `rep` consecutive steps of it.
+  const int steps_per_wave = (nsteps + NW - 1) / NW;
   const int rep = max(1, (steps_per_wave * NW + kMaxTiles - 1) / kMaxTiles);
   const int tiles_per_wave = (steps_per_wave + rep - 1) / rep;
-  const int ntiles = tiles_per_wave * NW;
-  const int wave = tid / kWave, lane = tid % kWave;
+  const int ntiles = resident ? nsteps : tiles_per_wave * NW;
 
-  auto step_group = [&](int w, int sw) {  // group of this lane in step sw of wave w, -1 = nothing there
+  auto step_group = [&](int w, int sw) {  // streamed slice: group of this lane in step sw of wave w, -1 = none
     const int gi = g_begin + (w * steps_per_wave + sw) * kWave + lane;
     return (sw < steps_per_wave && gi < g_end) ? gi : -1;
   };
@@ -542,25 +618,39 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   double total = 0.0, before = 0.0;
   int owner = 0;
   for (int attempt = 0; attempt < 2; ++attempt) {
-    // tile sums of this work-group's slice, kPassBatch steps of loads in flight at a time
-    double acc = 0.0;
-    for (int s0 = 0; s0 < steps_per_wave; s0 += kPassBatch) {
-      float z[kPassBatch][8], q[kPassBatch][8];
+    if (resident) {
+      refresh_resident();
 #pragma unroll
-      for (int i = 0; i < kPassBatch; ++i) {
-        const int gi = step_group(wave, s0 + i);
-        if (gi >= 0) rv.load(gi, z[i], q[i]);
+      for (int i = 0; i < kResident; ++i) {
+        const int s = i * NW + wave;
+        if (s < nsteps) {  // wave-uniform
+          const float gs = ((fc[i][0] + fc[i][1]) + (fc[i][2] + fc[i][3])) +
+                           ((fc[i][4] + fc[i][5]) + (fc[i][6] + fc[i][7]));
+          const double t = wave_sum(static_cast<double>(gs));
+          if (lane == 0) sh_tile[s] = t;
+        }
       }
+    } else {
+      // tile sums of this work-group's slice, kPassBatch steps of loads in flight at a time
+      double acc = 0.0;
+      for (int s0 = 0; s0 < steps_per_wave; s0 += kPassBatch) {
+        float z[kPassBatch][8], q[kPassBatch][8];
 #pragma unroll
-      for (int i = 0; i < kPassBatch; ++i) {
-        const int sw = s0 + i;
-        if (sw < steps_per_wave) {
-          const int gi = step_group(wave, sw);
-          if (gi >= 0) { float f[8]; acc += static_cast<double>(group_sum(z[i], q[i], gi, f)); }
-          if ((sw + 1) % rep == 0 || sw + 1 == steps_per_wave) {
-            const double t = wave_sum(acc);
-            if (lane == 0) sh_tile[wave * tiles_per_wave + sw / rep] = t;
-            acc = 0.0;
+        for (int i = 0; i < kPassBatch; ++i) {
+          const int gi = step_group(wave, s0 + i);
+          if (gi >= 0) rv.load(gi, z[i], q[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < kPassBatch; ++i) {
+          const int sw = s0 + i;
+          if (sw < steps_per_wave) {
+            const int gi = step_group(wave, sw);
+            if (gi >= 0) { float f[8]; acc += static_cast<double>(group_sum(z[i], q[i], gi, f)); }
+            if ((sw + 1) % rep == 0 || sw + 1 == steps_per_wave) {
+              const double t = wave_sum(acc);
+              if (lane == 0) sh_tile[wave * tiles_per_wave + sw / rep] = t;
+              acc = 0.0;
+            }
           }
         }
       }
@@ -596,6 +686,8 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
       if (j == rv.ch.n - 1) rv.ch.rinv[j] = 0.0f;
     pending_norm = false;
     last_norm = 0.0f;
+    have = false;
+    applied = 0;
     __syncthreads();
   }
   if (pending_norm) last_norm = static_cast<float>(total);
@@ -604,14 +696,13 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
     a.len[b] = plen;
     if (a.status) a.status[b] = sh_flag ? MARS_REQ_TIMEOUT : MARS_REQ_OK;
   }
-  if (g != owner || wave != 0) return;
+  if (g != owner) return;
 
-  // Wave 0 of the owning work-group: locate the tile, then the element.
-  int pick = -1;
-  float pick_f = 0.0f;
+  // The owning work-group locates the tile (every wave does, from the same LDS values).
+  int tile = -1;
+  double cum = before;
   if (total > 0.0) {
-    double cum = before;
-    int tile = -1, last_tile = -1;
+    int last_tile = -1;
     for (int t = 0; t < ntiles; ++t) {
       if (sh_tile[t] > 0.0) last_tile = t;
       if (tile < 0) {
@@ -623,20 +714,45 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
       cum = before;
       for (int t = 0; t < tile; ++t) cum += sh_tile[t];
     }
-    const int tw = tile / tiles_per_wave, ts = (tile % tiles_per_wave) * rep;
+  }
+  // One wave finishes: the one holding the tile in registers, or wave 0 re-reading it.
+  const int finder = (resident && tile >= 0) ? tile % NW : 0;
+  if (wave != finder) return;
+
+  int pick = -1;
+  float pick_f = 0.0f;
+  if (total > 0.0) {
+    const int tw = resident ? 0 : tile / tiles_per_wave, ts = resident ? 0 : (tile % tiles_per_wave) * rep;
+    const int nrep = resident ? 1 : rep;
     int last_pos_v = -1;
     float last_pos_f = 0.0f;
-    for (int r = 0; r < rep && pick < 0; ++r) {
-      const int gi = step_group(tw, ts + r);
+    for (int r = 0; r < nrep && pick < 0; ++r) {
+      int gi;
       float f[8];
       float gs = 0.0f;
-      if (gi >= 0) {
-        float z[8], q[8];
-        rv.load(gi, z, q);
-        gs = group_sum(z, q, gi, f);
-      } else {
+      if (resident) {
+        const int ii = tile / NW;
+        gi = g_begin + ii * NT + tid;
+        if (gi >= g_end) gi = -1;
 #pragma unroll
         for (int e = 0; e < 8; ++e) f[e] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kResident; ++i)
+          if (i == ii) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] = fc[i][e];
+          }
+        gs = ((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7]));
+      } else {
+        gi = step_group(tw, ts + r);
+        if (gi >= 0) {
+          float z[8], q[8];
+          rv.load(gi, z, q);
+          gs = group_sum(z, q, gi, f);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) f[e] = 0.0f;
+        }
       }
       double gincl = static_cast<double>(gs);
 #pragma unroll
