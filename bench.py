@@ -57,6 +57,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="for hardware-counter runs: a few launches of the row reduction on the headline "
+                         "workload and of a plain device copy of the same size (the calibration kernel)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU only: the verification pass is per request and needs no "
@@ -98,6 +101,17 @@ def main() -> int:
 
     ws = M.alloc_workspace(B, N, V, dev)
     out = M.VerifyOutputs(B, N, dev)
+
+    if args.pmc_probe:
+        # Counter runs serialise kernels; keep the run short.  The copy moves exactly the bytes of one
+        # logits tensor (read) and as many again (write): the known quantity the counters are scaled by.
+        dst = torch.empty_like(sets[0]["logits"])
+        for i in range(6):
+            dst.copy_(sets[i % N_BUFFERS]["logits"])
+            M.mars_row_reduce(sets[i % N_BUFFERS]["logits"], T, ws)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_probe": True, "logits_bytes": rows * V * elt, "launches_each": 6}), flush=True)
+        return 0
 
     def step(i):
         s = sets[i % N_BUFFERS]

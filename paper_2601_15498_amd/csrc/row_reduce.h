@@ -15,27 +15,49 @@
 
 namespace mars {
 
-constexpr int kRowThreads = 256;  // 4 waves per work-group
-constexpr int kUnroll = 4;        // 16-byte loads per lane per batch
+#ifndef MARS_ROW_THREADS
+#define MARS_ROW_THREADS 256
+#endif
+#ifndef MARS_ROW_UNROLL
+#define MARS_ROW_UNROLL 4
+#endif
+constexpr int kRowThreads = MARS_ROW_THREADS;  // 4 waves per work-group
+constexpr int kUnroll = MARS_ROW_UNROLL;       // 16-byte loads per lane per batch
 constexpr float kRescaleLog2 = 24.0f;  // move the sum-exp reference when the max rises by 2^24
 
-// Exact (value desc, index asc) top-2 among the elements of the lane's batch `batch` whose
-// value is >= cut, merged into (k1, k2).
+// Exact (value desc, index asc) top-2 among the elements >= cut of the lane's batches b1 and
+// (when two == true) b2, merged into (k1, k2).  All loads are issued before the first use: the
+// rescan sits at the very end of a work-group's life, where a dependent round trip per vector
+// would be paid in full.
 template <typename T, int EPV>
-__device__ void scan_batch(const T* __restrict__ rowp, int v_begin, int v_end, int batch, int tid, float cut,
-                           unsigned long long& k1, unsigned long long& k2) {
+__device__ void scan_batches(const T* __restrict__ rowp, int v_begin, int v_end, int b1, int b2, bool two, int tid,
+                             float cut, unsigned long long& k1, unsigned long long& k2) {
+  Vec<T, EPV> va[kUnroll], vb[kUnroll];
+#pragma unroll
   for (int j = 0; j < kUnroll; ++j) {
-    const int vec = v_begin + (batch * kUnroll + j) * kRowThreads + tid;
-    if (vec < v_end) {
-      Vec<T, EPV> v;
-      v.load(rowp, static_cast<unsigned int>(vec));
+    const int veca = v_begin + (b1 * kUnroll + j) * kRowThreads + tid;
+    if (veca < v_end) va[j].load(rowp, static_cast<unsigned int>(veca)); else va[j].fill_neg_inf();
+    const int vecb = v_begin + (b2 * kUnroll + j) * kRowThreads + tid;
+    if (two && vecb < v_end) vb[j].load(rowp, static_cast<unsigned int>(vecb)); else vb[j].fill_neg_inf();
+  }
+  // Only a vector whose maximum reaches the cut is looked at element by element (normally one
+  // or two of them): the insertions are a serial chain run by a wave with one or two live lanes.
+  auto scan_vec = [&](const Vec<T, EPV>& v, int vec) {
+    float vm = v.get(0);
+#pragma unroll
+    for (int e = 1; e < EPV; ++e) vm = fmaxf(vm, v.get(e));
+    if (vm >= cut) {
 #pragma unroll
       for (int e = 0; e < EPV; ++e) {
         const float x = v.get(e);
         if (x >= cut) top2_insert(k1, k2, make_key(x, vec * EPV + e));
       }
     }
-  }
+  };
+#pragma unroll
+  for (int j = 0; j < kUnroll; ++j) scan_vec(va[j], v_begin + (b1 * kUnroll + j) * kRowThreads + tid);
+#pragma unroll
+  for (int j = 0; j < kUnroll; ++j) scan_vec(vb[j], v_begin + (b2 * kUnroll + j) * kRowThreads + tid);
 }
 
 template <typename T, int EPV, bool SAMPLING>
@@ -207,8 +229,7 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   const float cut = L2 > neg_inf() ? L2 : -3.4028235e38f;
   if (Z1 > neg_inf() && m1 >= cut) {
     unsigned long long k1 = 0, k2 = 0;
-    scan_batch<T, EPV>(rowp, v_begin, v_end, b1, tid, cut, k1, k2);
-    if (m2 >= cut) scan_batch<T, EPV>(rowp, v_begin, v_end, b2, tid, cut, k1, k2);
+    scan_batches<T, EPV>(rowp, v_begin, v_end, b1, b2, m2 >= cut, tid, cut, k1, k2);
     const int n = (k1 != 0) + (k2 != 0);
     const int slot = atomicAdd(&sh_ncand, n);
     if (k1 != 0) sh_cand[slot] = k1;
@@ -236,7 +257,7 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
       float S = 0.0f;
 #pragma unroll
       for (int w = 0; w < NW; ++w)  // exact power-of-two scalings
-        if (sh_sum[w] > 0.0f) S += ldexpf(sh_sum[w], static_cast<int>(fmaxf(sh_ref[w] - R, -300.0f)));
+        if (sh_sum[w] > 0.0f) S += __builtin_ldexpf(sh_sum[w], static_cast<int>(fmaxf(sh_ref[w] - R, -300.0f)));
       out.s = S; out.ref = S > 0.0f ? R : 0.0f;
     }
     partials[item] = out;
