@@ -85,10 +85,13 @@ __device__ __forceinline__ float key_value(unsigned long long k) { return unord_
 __device__ __forceinline__ int key_index(unsigned long long k) {
   return static_cast<int>(0xFFFFFFFFu - static_cast<uint32_t>(k & 0xFFFFFFFFull));
 }
-// Insert a key into a running (k1 >= k2) pair.
+// Insert a key into a running (k1 >= k2) pair.  Written with selects on the values: as two
+// conditional assignments the compiler merges the stores into one store through a selected
+// address, which pins k1 and k2 to scratch memory.
 __device__ __forceinline__ void top2_insert(unsigned long long& k1, unsigned long long& k2, unsigned long long k) {
-  if (k > k1) { k2 = k1; k1 = k; }
-  else if (k > k2) { k2 = k; }
+  const bool first = k > k1, second = k > k2;
+  k2 = first ? k1 : (second ? k : k2);
+  k1 = first ? k : k1;
 }
 
 // ---------------------------------------------------------------- wave-level reductions (wave64)
@@ -160,8 +163,8 @@ __device__ __forceinline__ void wave_top2_values(float& a1, float& a2) {
   a1 = r1; a2 = r2;
 }
 
-// Per-(row, split) partial result of the row reduction.  id < 0 marks an absent
-// candidate (a split with fewer than two elements).  s is the partial sum of
+// Partial result of the row reduction for the share of a row one wave streamed.  id < 0 marks
+// an absent candidate (a share with fewer than two elements).  s is the partial sum of
 // exp2(z * c - ref) over the split; ref is integer-valued, so that sums taken against
 // different references are brought together by exact power-of-two scalings.
 struct Partial {

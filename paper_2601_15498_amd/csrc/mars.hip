@@ -56,7 +56,7 @@ static Layout layout(int B, int N, int V) {
   const long rows = static_cast<long>(B) * N;
   L.splits = choose_splits(rows, V);
   L.partials_off = 0;
-  L.stats_off = align_up(static_cast<size_t>(rows) * L.splits * sizeof(Partial));
+  L.stats_off = align_up(static_cast<size_t>(rows) * L.splits * kPartsPerItem * sizeof(Partial));
   L.G = choose_groups(B, V);
   L.xslots_off = L.stats_off + align_up(static_cast<size_t>(rows) * sizeof(mars_row_stat));
   L.total = L.xslots_off + align_up(static_cast<size_t>(B) * (N + 2) * 2 * L.G * sizeof(unsigned long long));
@@ -161,7 +161,7 @@ int mars_row_stats(const void* logits, int logits_dtype, const float* theta, flo
     return MARS_ERR_HIP;
   const int threads = 256;
   hipLaunchKernelGGL(merge_stats_kernel, dim3(static_cast<unsigned int>((rows + threads - 1) / threads)),
-                     dim3(threads), 0, stream, partials, static_cast<int>(rows), N, L.splits, theta, c, stats);
+                     dim3(threads), 0, stream, partials, static_cast<int>(rows), N, L.splits * kPartsPerItem, theta, c, stats);
   return hipGetLastError() == hipSuccess ? MARS_OK : MARS_ERR_HIP;
 }
 
@@ -206,7 +206,7 @@ int mars_verify(const void* logits, int logits_dtype, const int32_t* draft_token
   a.xslots = xslots;
   a.mask = accept_mask; a.len = accept_len; a.path = path_idx; a.bonus = bonus_token;
   a.dec = decision; a.status = request_status; a.diag = diag;
-  a.B = B; a.N = N; a.V = V; a.splits = L.splits; a.c = c;
+  a.B = B; a.N = N; a.V = V; a.splits = L.splits * kPartsPerItem; a.c = c;
 
   if (!sampling) {
     hipLaunchKernelGGL(tail_greedy_kernel, dim3(static_cast<unsigned int>(B)), dim3(kGreedyThreads), 0, stream, a);

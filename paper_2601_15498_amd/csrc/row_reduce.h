@@ -1,4 +1,4 @@
-// Row reduction: per (row, split) the two largest logits with their indices under
+// Row reduction: per (row, split, wave) the two largest logits with their indices under
 // (value desc, index asc) and, in sampling mode, the sum of exp2(z*c - ref).
 // One streaming read of the logits; this is the HBM-bound kernel of the pass
 // (paper Sec. 3.3 top-2 identification, Eq. 3 softmax normaliser).
@@ -6,9 +6,14 @@
 // The per-element work is kept to the minimum the arithmetic units can hide behind the
 // memory stream: widen, half a max3 and, when sampling, one fma + exp2 + add.  A lane only
 // tracks the maxima of its batches (32 elements each): the best and second-best batch
-// maximum and the batches they came from.  A lane's two largest elements are then known to
-// lie in those two batches, so after the stream the few lanes that can hold a row-level
-// candidate reload one or two batches and produce exact (value, index) pairs.
+// maximum and the batches they came from, and keeps a raw copy of its best batch in LDS.
+// A lane's two largest elements are then known to lie in those two batches, so after the
+// stream the few lanes that can hold a candidate look through their LDS copy (and, rarely,
+// reload the second batch) and produce exact (value, index) pairs.
+//
+// Every wave works for itself from the first load to its own partial result: there is no
+// barrier and no cross-wave traffic in the kernel, so a wave that has finished leaves the
+// memory pipeline to the others instead of holding them at a rendezvous.
 #pragma once
 
 #include "common.h"
@@ -25,39 +30,53 @@ constexpr int kRowThreads = MARS_ROW_THREADS;  // 4 waves per work-group
 constexpr int kUnroll = MARS_ROW_UNROLL;       // 16-byte loads per lane per batch
 constexpr float kRescaleLog2 = 24.0f;  // move the sum-exp reference when the max rises by 2^24
 
-// Exact (value desc, index asc) top-2 among the elements >= cut of the lane's batches b1 and
-// (when two == true) b2, merged into (k1, k2).  All loads are issued before the first use: the
-// rescan sits at the very end of a work-group's life, where a dependent round trip per vector
-// would be paid in full.
+// Insert the elements >= cut of one vector into the running key pair (k1 >= k2).  Only a
+// vector whose maximum reaches the cut is looked at element by element (normally one or two):
+// the insertions are a serial chain run by a wave with one or two live lanes.
 template <typename T, int EPV>
-__device__ void scan_batches(const T* __restrict__ rowp, int v_begin, int v_end, int b1, int b2, bool two, int tid,
-                             float cut, unsigned long long& k1, unsigned long long& k2) {
-  Vec<T, EPV> va[kUnroll], vb[kUnroll];
+__device__ __forceinline__ void scan_vec(const Vec<T, EPV>& v, int vec, float cut, unsigned long long& k1,
+                                         unsigned long long& k2) {
+  float vm = v.get(0);
 #pragma unroll
-  for (int j = 0; j < kUnroll; ++j) {
-    const int veca = v_begin + (b1 * kUnroll + j) * kRowThreads + tid;
-    if (veca < v_end) va[j].load(rowp, static_cast<unsigned int>(veca)); else va[j].fill_neg_inf();
-    const int vecb = v_begin + (b2 * kUnroll + j) * kRowThreads + tid;
-    if (two && vecb < v_end) vb[j].load(rowp, static_cast<unsigned int>(vecb)); else vb[j].fill_neg_inf();
+  for (int e = 1; e < EPV; ++e) vm = fmaxf(vm, v.get(e));
+  if (vm >= cut) {
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) {
+      const float x = v.get(e);
+      if (x >= cut) top2_insert(k1, k2, make_key(x, vec * EPV + e));
+    }
   }
-  // Only a vector whose maximum reaches the cut is looked at element by element (normally one
-  // or two of them): the insertions are a serial chain run by a wave with one or two live lanes.
-  auto scan_vec = [&](const Vec<T, EPV>& v, int vec) {
-    float vm = v.get(0);
-#pragma unroll
-    for (int e = 1; e < EPV; ++e) vm = fmaxf(vm, v.get(e));
-    if (vm >= cut) {
-#pragma unroll
-      for (int e = 0; e < EPV; ++e) {
-        const float x = v.get(e);
-        if (x >= cut) top2_insert(k1, k2, make_key(x, vec * EPV + e));
+}
+
+// Exact ranking of every element a lane owns (cold path, kept out of line).
+// (Results come back by value: a local whose address is handed to an out-of-line function lives in
+// scratch memory, and every later access to it becomes a memory round trip.)
+struct KeyPair { unsigned long long k1, k2; };
+template <typename T, int EPV>
+__device__ __noinline__ KeyPair rank_all(const T* __restrict__ rowp, int v_begin, int v_end, int nb, int tid) {
+  unsigned long long k1 = 0, k2 = 0;
+#pragma unroll 1
+  for (int kb = 0; kb < nb; ++kb) {
+#pragma unroll 1
+    for (int j = 0; j < kUnroll; ++j) {
+      const int vec = v_begin + (kb * kUnroll + j) * kRowThreads + tid;
+      if (vec < v_end) {
+        Vec<T, EPV> v;
+        v.load(rowp, static_cast<unsigned int>(vec));
+#pragma unroll 1
+        for (int e = 0; e < EPV; ++e) top2_insert(k1, k2, make_key(v.get(e), vec * EPV + e));
       }
     }
-  };
-#pragma unroll
-  for (int j = 0; j < kUnroll; ++j) scan_vec(va[j], v_begin + (b1 * kUnroll + j) * kRowThreads + tid);
-#pragma unroll
-  for (int j = 0; j < kUnroll; ++j) scan_vec(vb[j], v_begin + (b2 * kUnroll + j) * kRowThreads + tid);
+  }
+  KeyPair r;
+  r.k1 = k1; r.k2 = k2;
+  return r;
+}
+
+__device__ __forceinline__ unsigned long long lane_value(unsigned long long v, int lane) {
+  const unsigned int lo = __builtin_amdgcn_readlane(static_cast<int>(v), lane);
+  const unsigned int hi = __builtin_amdgcn_readlane(static_cast<int>(v >> 32), lane);
+  return (static_cast<unsigned long long>(hi) << 32) | lo;
 }
 
 template <typename T, int EPV, bool SAMPLING>
@@ -100,6 +119,9 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   float thresh = -3.0e38f;               // rescale when a lane maximum exceeds this (wave-uniform)
   const float tau_over_c = SAMPLING ? kRescaleLog2 / c : 0.0f;
 
+  // Raw copy of every lane's best batch (vector j of lane t at [j][t]: conflict-free 16-byte rows).
+  __shared__ Vec<T, EPV> sh_best[U][kRowThreads];
+
   Vec<T, EPV> bufA[U], bufB[U];
 
   // Unconditional loads for a full batch; bounds-checked loads (padding with -inf) for the last one.
@@ -107,6 +129,9 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
     const T* __restrict__ bp = rowp + static_cast<size_t>(v_begin + k * BV) * EPV;  // wave-uniform
 #pragma unroll
     for (int j = 0; j < U; ++j) buf[j].load(bp, static_cast<unsigned int>(tid + j * kRowThreads));
+    // Keep the scheduler from hoisting uses of the other buffer above these loads: that would
+    // turn the wait for the previous batch into a wait before this one is even issued.
+    __builtin_amdgcn_sched_barrier(0);
   };
   auto load_tail = [&](Vec<T, EPV>(&buf)[U], int k) {
     const int base = v_begin + k * BV + tid;
@@ -146,6 +171,12 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
     b2 = gt ? b1 : (g2 ? k : b2);
     m1 = gt ? bm : m1;
     b1 = gt ? k : b1;
+    if (__any(gt)) {
+      if (gt) {
+#pragma unroll
+        for (int j = 0; j < U; ++j) sh_best[j][tid] = buf[j];
+      }
+    }
     if (SAMPLING) {
       if (__any(m1 > thresh)) {
         // Rare: the wave's maximum rose more than 2^kRescaleLog2 above the reference (or this is
@@ -173,10 +204,11 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   };
 
   // Double-buffered stream over the full batches: the loads of batch k+1 are in flight while
-  // batch k is processed.  The ragged last batch (if any) is loaded with bounds checks.
-  const bool has_tail = nb > nfull;
+  // batch k is processed.  The last one to three batches (the ragged one among them) run
+  // through a plain loop with bounds-checked loads; keeping that part small keeps the kernel's
+  // code small, which matters for the cold code every wave runs once at its end.
   int k = 0;
-  if (nfull > 0) {
+  if (nfull > 2) {
     load_full(bufA, 0);
     for (; k + 2 < nfull; k += 2) {
       load_full(bufB, k + 1);
@@ -184,91 +216,79 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
       load_full(bufA, k + 2);
       process(bufB, k + 1);
     }
-    // one or two full batches left; bufA holds batch k
-    if (k + 1 < nfull) {
-      load_full(bufB, k + 1);
-      process(bufA, k);
-      if (has_tail) load_tail(bufA, nfull);
-      process(bufB, k + 1);
-      if (has_tail) process(bufA, nfull);
-    } else {
-      if (has_tail) load_tail(bufB, nfull);
-      process(bufA, k);
-      if (has_tail) process(bufB, nfull);
-    }
-  } else if (has_tail) {
-    load_tail(bufA, 0);
-    process(bufA, 0);
+    process(bufA, k);
+    ++k;
+  }
+#pragma unroll 1
+  for (; k < nb; ++k) {
+    load_tail(bufB, k);
+    process(bufB, k);
   }
 
-  // ------------------------------------------------------------------ work-group epilogue
-  __shared__ float sh_m1[NW], sh_m2[NW], sh_ref[NW], sh_sum[NW];
-  __shared__ unsigned long long sh_cand[4 * kRowThreads];
-  __shared__ int sh_ncand;
-
+  // ------------------------------------------------------------------ per-wave epilogue
   const int wave = tid / kWave, lane = tid % kWave;
   float w1 = m1, w2 = m2;
   wave_top2_values(w1, w2);
+  // w1 is the wave's maximum; w2, the second largest batch maximum over its lanes, is a lower
+  // bound of its runner-up.  Every element >= w2 lies in batch b1 or b2 of a lane whose own
+  // maxima reach w2: those lanes look through their batches.
+  unsigned long long k1 = 0, k2 = 0;
+  if (w2 > neg_inf()) {
+    const float cut = w2;
+    if (m1 >= cut) {
+#pragma unroll 1
+      for (int j = 0; j < U; ++j) {
+        const int vec = v_begin + (b1 * U + j) * kRowThreads + tid;
+        if (vec < v_end) scan_vec<T, EPV>(sh_best[j][tid], vec, cut, k1, k2);
+      }
+      if (m2 >= cut) {  // rare: both of the lane's batches matter; the second comes from memory
+#pragma unroll 1
+        for (int j = 0; j < U; ++j) {
+          const int vec = v_begin + (b2 * U + j) * kRowThreads + tid;
+          if (vec < v_end) {
+            Vec<T, EPV> v;
+            v.load(rowp, static_cast<unsigned int>(vec));
+            scan_vec<T, EPV>(v, vec, cut, k1, k2);
+          }
+        }
+      }
+    }
+  } else {
+    // The wave saw fewer than two finite batch maxima (a tiny or almost entirely masked share):
+    // every element it owns, -inf entries included, is ranked exactly.
+    const KeyPair r = rank_all<T, EPV>(rowp, v_begin, v_end, nb, tid);
+    k1 = r.k1; k2 = r.k2;
+  }
+  // Wave-level top-2 of the lanes' keys: walk the (few) lanes that hold any.
+  unsigned long long K1 = 0, K2 = 0;
+  unsigned long long holders = __ballot(k1 != 0ull);
+  while (holders != 0ull) {
+    const int l = __ffsll(static_cast<long long>(holders)) - 1;
+    holders &= holders - 1;
+    top2_insert(K1, K2, lane_value(k1, l));
+    const unsigned long long second = lane_value(k2, l);
+    if (second != 0ull) top2_insert(K1, K2, second);
+  }
   float ws = 0.0f;
   if (SAMPLING) ws = wave_sum(s);
   if (lane == 0) {
-    sh_m1[wave] = w1; sh_m2[wave] = w2;
-    sh_ref[wave] = ref_c; sh_sum[wave] = ws;
-  }
-  if (tid == 0) sh_ncand = 0;
-  __syncthreads();
-  float Z1 = sh_m1[0], L2 = sh_m2[0];
-#pragma unroll
-  for (int w = 1; w < NW; ++w) top2_merge_values(Z1, L2, sh_m1[w], sh_m2[w]);
-  // Z1 is the split's maximum; L2, the second largest batch maximum over all lanes, is a lower
-  // bound of its runner-up.  Every element >= L2 lies in batch b1 or b2 of a lane whose own
-  // maxima reach L2; those lanes rescan.  -inf entries (masked tokens, padding) are never
-  // searched: among them the order is the index order, known in closed form.
-  // (L2 == -inf only says that a single lane saw finite values in a single batch; the runner-up
-  // may still be finite inside that batch, so the scan then takes every finite element.)
-  const float cut = L2 > neg_inf() ? L2 : -3.4028235e38f;
-  if (Z1 > neg_inf() && m1 >= cut) {
-    unsigned long long k1 = 0, k2 = 0;
-    scan_batches<T, EPV>(rowp, v_begin, v_end, b1, b2, m2 >= cut, tid, cut, k1, k2);
-    const int n = (k1 != 0) + (k2 != 0);
-    const int slot = atomicAdd(&sh_ncand, n);
-    if (k1 != 0) sh_cand[slot] = k1;
-    if (k2 != 0) sh_cand[slot + 1] = k2;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    unsigned long long k1 = 0, k2 = 0;
-    const int n = sh_ncand;
-    for (int i = 0; i < n; ++i) top2_insert(k1, k2, sh_cand[i]);
-    const int first = v_begin * EPV, count = nv * EPV;
     Partial out;
     out.z1 = neg_inf(); out.id1 = -1; out.z2 = neg_inf(); out.id2 = -1; out.s = 0.0f; out.ref = 0.0f;
-    if (count > 0) {
-      if (k1 != 0) { out.z1 = key_value(k1); out.id1 = key_index(k1); }
-      else { out.id1 = first; }  // every element is -inf
-      if (k2 != 0) { out.z2 = key_value(k2); out.id2 = key_index(k2); }
-      else if (count > 1) { out.id2 = (out.id1 == first) ? first + 1 : first; }  // runner-up is a -inf entry
-    }
-    if (SAMPLING) {
-      float R = -3.0e38f;
-#pragma unroll
-      for (int w = 0; w < NW; ++w)
-        if (sh_sum[w] > 0.0f) R = fmaxf(R, sh_ref[w]);
-      float S = 0.0f;
-#pragma unroll
-      for (int w = 0; w < NW; ++w)  // exact power-of-two scalings
-        if (sh_sum[w] > 0.0f) S += __builtin_ldexpf(sh_sum[w], static_cast<int>(fmaxf(sh_ref[w] - R, -300.0f)));
-      out.s = S; out.ref = S > 0.0f ? R : 0.0f;
-    }
-    partials[item] = out;
+    if (K1 != 0ull) { out.z1 = key_value(K1); out.id1 = key_index(K1); }
+    if (K2 != 0ull) { out.z2 = key_value(K2); out.id2 = key_index(K2); }
+    if (SAMPLING && ws > 0.0f) { out.s = ws; out.ref = ref_c; }
+    partials[static_cast<size_t>(item) * NW + wave] = out;
   }
 }
 
-// One thread per row: merge the splits into the statistics table.
-__global__ void merge_stats_kernel(const Partial* __restrict__ partials, int rows, int N, int splits,
+// Partial results per (row, split): one per wave of the work-group.
+constexpr int kPartsPerItem = kRowThreads / kWave;
+
+// One thread per row: merge its partial results into the statistics table.
+__global__ void merge_stats_kernel(const Partial* __restrict__ partials, int rows, int N, int parts,
                                    const float* __restrict__ theta, float c, mars_row_stat* __restrict__ stats) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
-  if (r < rows) merge_row(partials + static_cast<size_t>(r) * splits, splits, theta[r / N], c, &stats[r]);
+  if (r < rows) merge_row(partials + static_cast<size_t>(r) * parts, parts, theta[r / N], c, &stats[r]);
 }
 
 }  // namespace mars

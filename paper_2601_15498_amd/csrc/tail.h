@@ -34,7 +34,7 @@ struct TailArgs {
   uint8_t* dec;          // optional
   int32_t* status;       // optional
   mars_req_diag* diag;   // optional
-  int B, N, V, splits;
+  int B, N, V, splits;   // splits = partial results per row
   float c;               // log2(e) / T, 0 in greedy mode
   // sampling mode: G work-groups share one request and exchange partial sums
   int G;
