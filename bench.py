@@ -26,7 +26,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 N_BUFFERS = 4
-PARTIAL_BYTES = 24     # one partial result per (row, split) written by the row reduction
+PARTIAL_BYTES = 24     # one partial result per (row, split, wave) written by the row reduction
+WAVES_PER_GROUP = 4    # waves per work-group of the row reduction
 
 
 def kernel_source_digest() -> str:
@@ -140,8 +141,8 @@ def main() -> int:
     e1.record()
     torch.cuda.synchronize()
     k1_ms = e0.elapsed_time(e1) / args.steps
-    splits = 1  # 960 rows: one work-group per row
-    algo_bytes = rows * V * elt + rows * splits * PARTIAL_BYTES
+    splits = max(1, min((1024 + rows - 1) // rows, V // 8192))  # the library's rule: 2 for 960 rows
+    algo_bytes = rows * V * elt + rows * splits * WAVES_PER_GROUP * PARTIAL_BYTES
     achieved = algo_bytes / (k1_ms * 1e-3) / 1e9
 
     result = {

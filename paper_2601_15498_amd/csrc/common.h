@@ -176,30 +176,50 @@ struct Partial {
   float   ref;
 };
 
-// Merge the splits of one row into the public statistics entry.
-// c = log2(e) / T (0 in greedy mode).
-__device__ __forceinline__ void merge_row(const Partial* __restrict__ p, int splits, float theta, float c,
+// Merge the partial results of one row into the public statistics entry.
+// c = log2(e) / T (0 in greedy mode).  The partials are read four at a time (one round trip
+// per four), their sums are brought to a common integer reference by exact power-of-two
+// scalings, and only the last step -- moving the reference to the row maximum -- needs an
+// exponential, of an argument split into its integer part (exact) and a fraction in
+// [-1/2, 1/2] (one fp32 exp2).
+__device__ __forceinline__ void merge_row(const Partial* __restrict__ p, int parts, float theta, float c,
                                           mars_row_stat* __restrict__ out) {
   unsigned long long k1 = 0, k2 = 0;
-  for (int s = 0; s < splits; ++s) {
-    if (p[s].id1 >= 0) top2_insert(k1, k2, make_key(p[s].z1, p[s].id1));
-    if (p[s].id2 >= 0) top2_insert(k1, k2, make_key(p[s].z2, p[s].id2));
+  float R = -3.0e38f;     // common reference: the largest one met so far
+  double S = 0.0;         // sum relative to R
+  for (int s0 = 0; s0 < parts; s0 += 4) {
+    Partial q[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (s0 + i < parts) q[i] = p[s0 + i];
+      else { q[i].id1 = -1; q[i].id2 = -1; q[i].s = 0.0f; q[i].ref = 0.0f; q[i].z1 = 0.0f; q[i].z2 = 0.0f; }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (q[i].id1 >= 0) top2_insert(k1, k2, make_key(q[i].z1, q[i].id1));
+      if (q[i].id2 >= 0) top2_insert(k1, k2, make_key(q[i].z2, q[i].id2));
+      if (c > 0.0f && q[i].s > 0.0f) {
+        if (q[i].ref > R) {  // move the running sum to the new, larger reference
+          S *= static_cast<double>(__builtin_ldexpf(1.0f, static_cast<int>(fmaxf(R - q[i].ref, -140.0f))));
+          R = q[i].ref;
+        }
+        S += static_cast<double>(__builtin_ldexpf(q[i].s, static_cast<int>(fmaxf(q[i].ref - R, -140.0f))));
+      }
+    }
   }
   const float z1 = key_value(k1), z2 = key_value(k2);
-  double S = 0.0;
-  if (c > 0.0f) {
-    float R = -3.0e38f;
-    for (int s = 0; s < splits; ++s)
-      if (p[s].s > 0.0f) R = fmaxf(R, p[s].ref);
-    for (int s = 0; s < splits; ++s)
-      if (p[s].s > 0.0f) S += ldexp(static_cast<double>(p[s].s), static_cast<int>(fmaxf(p[s].ref - R, -2000.0f)));
-    // S is relative to the integer reference R; move it to the row maximum (|R - z1*c| is small)
-    S *= exp2(static_cast<double>(R) - static_cast<double>(z1) * static_cast<double>(c));
+  float sum_exp = 0.0f;
+  if (c > 0.0f && S > 0.0) {
+    // S is relative to R; the row maximum z1 is the public reference: S * 2^(R - z1*c)
+    const double d = static_cast<double>(R) - static_cast<double>(z1) * static_cast<double>(c);
+    const double n = rint(d);
+    const float frac = static_cast<float>(d - n);
+    sum_exp = static_cast<float>(ldexp(S * static_cast<double>(__builtin_amdgcn_exp2f(frac)), static_cast<int>(n)));
   }
   mars_row_stat st;
   st.z1 = z1; st.id1 = key_index(k1);
   st.z2 = z2; st.id2 = key_index(k2);
-  st.sum_exp = static_cast<float>(S);
+  st.sum_exp = sum_exp;
   // Eq. 4 and the strict test r > theta, one correctly rounded fp32 division; no
   // relaxation outside the positive domain the paper assumes for z(1).
   st.relax_ok = (z1 > 0.0f && (z2 / z1) > theta) ? 1 : 0;

@@ -4,7 +4,6 @@
 
 #include <cmath>
 #include <cstdint>
-#include <cstdlib>
 
 #include "../../include/mars.h"
 #include "common.h"
@@ -22,7 +21,9 @@ static size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // Splits per row: a function of (rows, V) only, so that the workspace size does not depend on
 // the element type.
 static int choose_splits(long rows, int V) {
-  if (const char* e = getenv("MARS_SPLITS_TUNE")) { int v = atoi(e); if (v > 0) return v; }
+#ifdef MARS_FORCE_SPLITS  // build-time tuning hook
+  return MARS_FORCE_SPLITS;
+#endif
   long want = (kTargetItems + rows - 1) / rows;
   long cap = V / kMinSplitElems;
   if (cap < 1) cap = 1;
@@ -42,7 +43,6 @@ struct Layout {
 // 4096 vocabulary entries long.
 constexpr int kComputeUnits = 256;
 static int choose_groups(int B, int V) {
-  if (const char* e = getenv("MARS_GROUPS_TUNE")) { int v = atoi(e); if (v > 0) return v > kMaxGroupsPerRequest ? kMaxGroupsPerRequest : v; }
   int G = kComputeUnits / B;
   const int cap = V / 4096;
   if (G > cap) G = cap;

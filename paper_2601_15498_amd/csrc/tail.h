@@ -355,8 +355,7 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   __shared__ double sh_red[NW];
   __shared__ double sh_part[kMaxGroupsPerRequest];
   __shared__ double sh_tile[kMaxTiles];
-  __shared__ int sh_accept;                      // decision code of the child under test
-  __shared__ float sh_fx;                        // f(x) of the child under test
+  __shared__ float sh_u[MARS_MAX_NODES + 1];     // the request's uniforms
   __shared__ int sh_flag;                        // exchange timed out
   __shared__ int sh_bad;                         // validation bits of the request
 
@@ -409,6 +408,7 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
       sh_qx[i] = qx;
       if (bad) atomicOr(&sh_bad, bad);
     }
+    for (int i = tid; i <= N; i += NT) sh_u[i] = a.u[static_cast<size_t>(b) * (N + 1) + i];
   }
   __syncthreads();
   if (sh_bad != 0) {
@@ -431,7 +431,7 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   constexpr bool resident = RESIDENT;
   const int nsteps = (g_end - g_begin + kWave - 1) / kWave;
   const float c = a.c;
-  const float* __restrict__ u = a.u + static_cast<size_t>(b) * (N + 1);
+  const float* u = sh_u;
 
   int cnode = 0, plen = 0, passes = 0, nexch = 0;
   float last_norm = 0.0f;
@@ -516,28 +516,22 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
       bool more = bits != 0ull;          // does cnode have further children after k?
       for (int w2 = wd + 1; w2 < nwords && !more; ++w2) more = sh_kids[w2] != 0ull;
       const int x = sh_tok[k];
-      if (tid == 0) {
-        int code = 0;
-        float fx = 0.0f;
-        if (x == st.id2 && st.relax_ok) {
-          code = MARS_DEC_RELAXED;  // runner-up in a low-margin row: accepted outright
-        } else {
-          const float qx = sh_qx[k];
-          fx = eval_f(sh_zx[k], qx, x, st.z1, c, rv.inv_S, dense, rv.ch);
-          // Eq. 1: accept with probability min(1, f(x)/q(x))
-          float acc;
-          if (fx == 0.0f) acc = 0.0f;
-          else if (qx <= 0.0f) acc = 1.0f;
-          else acc = fminf(1.0f, fx / qx);
-          if (u[k] < acc) code = MARS_DEC_SAMPLED;
-        }
-        sh_accept = code;
-        sh_fx = fx;
+      // Every thread takes the decision for itself from the same LDS-resident inputs (same
+      // instructions, same bits): no broadcast and no barrier per tested child.
+      int code = 0;
+      float fx = 0.0f;
+      if (x == st.id2 && st.relax_ok) {
+        code = MARS_DEC_RELAXED;  // runner-up in a low-margin row: accepted outright
+      } else {
+        const float qx = sh_qx[k];
+        fx = eval_f(sh_zx[k], qx, x, st.z1, c, rv.inv_S, dense, rv.ch);
+        // Eq. 1: accept with probability min(1, f(x)/q(x))
+        float acc;
+        if (fx == 0.0f) acc = 0.0f;
+        else if (qx <= 0.0f) acc = 1.0f;
+        else acc = fminf(1.0f, fx / qx);
+        if (u[k] < acc) code = MARS_DEC_SAMPLED;
       }
-      __syncthreads();
-      const int code = sh_accept;
-      const float fx = sh_fx;
-      __syncthreads();  // everyone has read the decision before thread 0 may overwrite it
       if (code) {
         if (tid == 0 && g == 0) {
           a.mask[rb + k] = 1;
