@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 N_BUFFERS = 4
 PARTIAL_BYTES = 24     # one partial result per (row, split, wave) written by the row reduction
-WAVES_PER_GROUP = 4    # waves per work-group of the row reduction
+WAVES_PER_GROUP = 8    # waves per work-group of the row reduction
 
 
 def kernel_source_digest() -> str:

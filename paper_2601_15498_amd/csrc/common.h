@@ -176,41 +176,16 @@ struct Partial {
   float   ref;
 };
 
-// Merge the partial results of one row into the public statistics entry.
-// c = log2(e) / T (0 in greedy mode).  The partials are read four at a time (one round trip
-// per four), their sums are brought to a common integer reference by exact power-of-two
-// scalings, and only the last step -- moving the reference to the row maximum -- needs an
-// exponential, of an argument split into its integer part (exact) and a fraction in
-// [-1/2, 1/2] (one fp32 exp2).
-__device__ __forceinline__ void merge_row(const Partial* __restrict__ p, int parts, float theta, float c,
-                                          mars_row_stat* __restrict__ out) {
-  unsigned long long k1 = 0, k2 = 0;
-  float R = -3.0e38f;     // common reference: the largest one met so far
-  double S = 0.0;         // sum relative to R
-  for (int s0 = 0; s0 < parts; s0 += 4) {
-    Partial q[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (s0 + i < parts) q[i] = p[s0 + i];
-      else { q[i].id1 = -1; q[i].id2 = -1; q[i].s = 0.0f; q[i].ref = 0.0f; q[i].z1 = 0.0f; q[i].z2 = 0.0f; }
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (q[i].id1 >= 0) top2_insert(k1, k2, make_key(q[i].z1, q[i].id1));
-      if (q[i].id2 >= 0) top2_insert(k1, k2, make_key(q[i].z2, q[i].id2));
-      if (c > 0.0f && q[i].s > 0.0f) {
-        if (q[i].ref > R) {  // move the running sum to the new, larger reference
-          S *= static_cast<double>(__builtin_ldexpf(1.0f, static_cast<int>(fmaxf(R - q[i].ref, -140.0f))));
-          R = q[i].ref;
-        }
-        S += static_cast<double>(__builtin_ldexpf(q[i].s, static_cast<int>(fmaxf(q[i].ref - R, -140.0f))));
-      }
-    }
-  }
+// Finish one row: the merged keys and the sum S (relative to the integer reference R) become
+// the public statistics entry.  Moving the reference to the row maximum needs the only
+// exponential of the merge, of an argument split into its integer part (exact) and a
+// fraction in [-1/2, 1/2] (one fp32 exp2).
+__device__ __forceinline__ mars_row_stat finish_row(unsigned long long k1, unsigned long long k2, float R, double S,
+                                                    float theta, float c) {
   const float z1 = key_value(k1), z2 = key_value(k2);
   float sum_exp = 0.0f;
   if (c > 0.0f && S > 0.0) {
-    // S is relative to R; the row maximum z1 is the public reference: S * 2^(R - z1*c)
+    // S * 2^(R - z1*c)
     const double d = static_cast<double>(R) - static_cast<double>(z1) * static_cast<double>(c);
     const double n = rint(d);
     const float frac = static_cast<float>(d - n);
@@ -223,7 +198,69 @@ __device__ __forceinline__ void merge_row(const Partial* __restrict__ p, int par
   // Eq. 4 and the strict test r > theta, one correctly rounded fp32 division; no
   // relaxation outside the positive domain the paper assumes for z(1).
   st.relax_ok = (z1 > 0.0f && (z2 / z1) > theta) ? 1 : 0;
-  *out = st;
+  return st;
+}
+
+// Sum S (relative to reference R) absorbs a partial sum s taken against reference ref; both
+// references are integers, so the scalings are exact powers of two.
+__device__ __forceinline__ void absorb_sum(float& R, double& S, float ref, double s) {
+  if (ref > R) {
+    S *= static_cast<double>(__builtin_ldexpf(1.0f, static_cast<int>(fmaxf(R - ref, -140.0f))));
+    R = ref;
+  }
+  S += s * static_cast<double>(__builtin_ldexpf(1.0f, static_cast<int>(fmaxf(ref - R, -140.0f))));
+}
+
+template <int CTRL>
+__device__ __forceinline__ unsigned long long dpp_move(unsigned long long v) {
+  const int lo = __builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, true);
+  const int hi = __builtin_amdgcn_update_dpp(0, static_cast<int>(v >> 32), CTRL, 0xF, 0xF, true);
+  return (static_cast<unsigned long long>(static_cast<unsigned int>(hi)) << 32) | static_cast<unsigned int>(lo);
+}
+
+// Cooperative merge of the partial results of rows [0, nrows): sixteen consecutive lanes (one
+// DPP row) take one row, each lane reads every sixteenth partial (coalesced, one round trip
+// when a row has at most sixteen), and a butterfly inside the DPP row merges keys and sums.
+// Every lane of the sixteen ends with the row's result; lane 0 of them hands it to `emit`.
+// Must be called by all NT threads of the work-group (NT a multiple of 64).
+template <int NT, typename ThetaAt, typename Emit>
+__device__ __forceinline__ void merge_rows_coop(const Partial* __restrict__ partials, int nrows, int parts,
+                                                float c, ThetaAt theta_at, Emit emit) {
+  const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  constexpr int kGroups = NT / 16;
+  for (int row0 = 0; row0 < nrows; row0 += kGroups) {
+    const int row = row0 + grp;
+    const bool live = row < nrows;
+    unsigned long long k1 = 0, k2 = 0;
+    float R = -3.0e38f;
+    double S = 0.0;
+    if (live) {
+      const Partial* __restrict__ p = partials + static_cast<size_t>(row) * parts;
+      for (int s = sub; s < parts; s += 16) {
+        const Partial q = p[s];
+        if (q.id1 >= 0) top2_insert(k1, k2, make_key(q.z1, q.id1));
+        if (q.id2 >= 0) top2_insert(k1, k2, make_key(q.z2, q.id2));
+        if (c > 0.0f && q.s > 0.0f) absorb_sum(R, S, q.ref, static_cast<double>(q.s));
+      }
+    }
+    // Butterfly over the sixteen lanes: at every step the two sides hold disjoint sets of
+    // elements, so no key can be inserted twice.  (All lanes take part; dead rows carry nothing.)
+#define MARS_MERGE_STEP(CTRL)                                                    \
+    {                                                                            \
+      const unsigned long long o1 = dpp_move<CTRL>(k1), o2 = dpp_move<CTRL>(k2); \
+      const float oR = dpp_move<CTRL>(R);                                        \
+      const double oS = dpp_move<CTRL>(S);                                       \
+      top2_insert(k1, k2, o1);                                                   \
+      top2_insert(k1, k2, o2);                                                   \
+      if (oS > 0.0) absorb_sum(R, S, oR, oS);                                    \
+    }
+    MARS_MERGE_STEP(kDppXor1)
+    MARS_MERGE_STEP(kDppXor2)
+    MARS_MERGE_STEP(kDppHalfMirror)
+    MARS_MERGE_STEP(kDppMirror)
+#undef MARS_MERGE_STEP
+    if (live && sub == 0) emit(row, finish_row(k1, k2, R, S, theta_at(row), c));
+  }
 }
 
 }  // namespace mars

@@ -159,8 +159,8 @@ int mars_row_stats(const void* logits, int logits_dtype, const float* theta, flo
   if (launch_row_reduce(logits, logits_dtype, rows, V, L.splits, temperature > 0.0f, c, partials, xslots, N, 2 * L.G,
                         stream) != hipSuccess)
     return MARS_ERR_HIP;
-  const int threads = 256;
-  hipLaunchKernelGGL(merge_stats_kernel, dim3(static_cast<unsigned int>((rows + threads - 1) / threads)),
+  const int threads = 256, rows_per_group = 16;
+  hipLaunchKernelGGL(merge_stats_kernel, dim3(static_cast<unsigned int>((rows + rows_per_group - 1) / rows_per_group)),
                      dim3(threads), 0, stream, partials, static_cast<int>(rows), N, L.splits * kPartsPerItem, theta, c, stats);
   return hipGetLastError() == hipSuccess ? MARS_OK : MARS_ERR_HIP;
 }

@@ -5,7 +5,7 @@
 //
 // The per-element work is kept to the minimum the arithmetic units can hide behind the
 // memory stream: widen, half a max3 and, when sampling, one fma + exp2 + add.  A lane only
-// tracks the maxima of its batches (32 elements each): the best and second-best batch
+// tracks the maxima of its batches (two 16-byte vectors each): the best and second-best batch
 // maximum and the batches they came from, and keeps a raw copy of its best batch in LDS.
 // A lane's two largest elements are then known to lie in those two batches, so after the
 // stream the few lanes that can hold a candidate look through their LDS copy (and, rarely,
@@ -21,12 +21,12 @@
 namespace mars {
 
 #ifndef MARS_ROW_THREADS
-#define MARS_ROW_THREADS 256
+#define MARS_ROW_THREADS 512
 #endif
 #ifndef MARS_ROW_UNROLL
-#define MARS_ROW_UNROLL 4
+#define MARS_ROW_UNROLL 2
 #endif
-constexpr int kRowThreads = MARS_ROW_THREADS;  // 4 waves per work-group
+constexpr int kRowThreads = MARS_ROW_THREADS;  // 8 waves per work-group (512 x 2 measured best of {128..1024} x {1,2,4,8})
 constexpr int kUnroll = MARS_ROW_UNROLL;       // 16-byte loads per lane per batch
 constexpr float kRescaleLog2 = 24.0f;  // move the sum-exp reference when the max rises by 2^24
 
@@ -285,10 +285,16 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
 constexpr int kPartsPerItem = kRowThreads / kWave;
 
 // One thread per row: merge its partial results into the statistics table.
-__global__ void merge_stats_kernel(const Partial* __restrict__ partials, int rows, int N, int parts,
-                                   const float* __restrict__ theta, float c, mars_row_stat* __restrict__ stats) {
-  const int r = blockIdx.x * blockDim.x + threadIdx.x;
-  if (r < rows) merge_row(partials + static_cast<size_t>(r) * parts, parts, theta[r / N], c, &stats[r]);
+__global__ __launch_bounds__(256) void merge_stats_kernel(const Partial* __restrict__ partials, int rows, int N,
+                                                          int parts, const float* __restrict__ theta, float c,
+                                                          mars_row_stat* __restrict__ stats) {
+  // 16 rows per work-group of 256 threads
+  const int first = blockIdx.x * 16;
+  const int n = min(16, rows - first);
+  if (n <= 0) return;
+  merge_rows_coop<256>(partials + static_cast<size_t>(first) * parts, n, parts, c,
+                       [&](int row) { return theta[(first + row) / N]; },
+                       [&](int row, const mars_row_stat& st) { stats[first + row] = st; });
 }
 
 }  // namespace mars

@@ -48,17 +48,18 @@ struct TailArgs {
 template <int NT>
 __device__ int merge_and_validate(const TailArgs& a, int b, bool write_user_stats) {
   const int N = a.N;
+  const size_t rb = static_cast<size_t>(b) * N;
   const float theta = a.theta[b];
+  merge_rows_coop<NT>(a.partials + rb * a.splits, N, a.splits, a.c, [&](int) { return theta; },
+                      [&](int row, const mars_row_stat& st) {
+                        // Several work-groups of a request may write the workspace copy: identical bits.
+                        a.stats_ws[rb + row] = st;
+                        if (write_user_stats && a.stats) a.stats[rb + row] = st;
+                      });
   int bad = 0;
   for (int i = threadIdx.x; i < N; i += NT) {
-    const size_t r = static_cast<size_t>(b) * N + i;
-    mars_row_stat st;
-    merge_row(a.partials + r * a.splits, a.splits, theta, a.c, &st);
-    // Several work-groups of a request may write the workspace copy: they write identical bits.
-    a.stats_ws[r] = st;
-    if (write_user_stats && a.stats) a.stats[r] = st;
-    const int p = a.par[r];
-    const int t = a.tok[r];
+    const int p = a.par[rb + i];
+    const int t = a.tok[rb + i];
     if (i == 0) { if (p != -1) bad |= 1; }
     else {
       if (p < 0 || p >= i) bad |= 1;
@@ -375,40 +376,54 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   // Prologue, one node per thread: validate tree and token, start the two gathers every
   // acceptance test needs (logit and draft probability of the node's token in its parent's
   // row: one round trip for the whole tree instead of one per visited node), and merge the
-  // row partials while those loads are in flight.  Every work-group of the request does this
-  // for itself; they produce identical bits, and only the first writes the caller's outputs.
+  // row partials (sixteen lanes per row) while those loads are in flight.  Every work-group of the
+  // request does this for itself; they produce identical bits, and only the first writes the
+  // caller's outputs.
   {
+    constexpr int kPerThread = (MARS_MAX_NODES + NT - 1) / NT;
     const float theta = a.theta[b];
-    for (int i = tid; i < N; i += NT) {
-      const size_t r = rb + i;
-      const int p = a.par[r];
-      const int x = a.tok[r];
-      int bad = 0;
-      if (i == 0) { if (p != -1) bad = 1; }
-      else {
-        if (p < 0 || p >= i) bad |= 1;
-        if (x < 0 || x >= V) bad |= 2;
+    float zx[kPerThread], qx[kPerThread];
+#pragma unroll
+    for (int t = 0; t < kPerThread; ++t) {
+      const int i = tid + t * NT;
+      zx[t] = 0.0f; qx[t] = 1.0f;
+      if (i < N) {
+        const size_t r = rb + i;
+        const int p = a.par[r];
+        const int x = a.tok[r];
+        int bad = 0;
+        if (i == 0) { if (p != -1) bad = 1; }
+        else {
+          if (p < 0 || p >= i) bad |= 1;
+          if (x < 0 || x >= V) bad |= 2;
+        }
+        const size_t at = (i > 0 && bad == 0) ? static_cast<size_t>(p) * V + x : 0;
+        zx[t] = widen(zall[at]);                 // consumed after the merge below
+        if (dense) qx[t] = widen(qall[at]);
+        sh_par[i] = static_cast<int16_t>(p);
+        sh_tok[i] = x;
+        if (bad) atomicOr(&sh_bad, bad);
+        if (g == 0) {
+          a.mask[r] = i == 0 ? 1 : 0;
+          a.path[r] = -1;
+          if (a.dec) a.dec[r] = 0;
+        }
       }
-      const size_t at = (i > 0 && bad == 0) ? static_cast<size_t>(p) * V + x : 0;
-      const float zx = widen(zall[at]);
-      const float qx = dense ? widen(qall[at]) : 1.0f;
-      mars_row_stat st;
-      merge_row(a.partials + r * a.splits, a.splits, theta, a.c, &st);
-      sh_st[i] = st;
-      if (g == 0) {
-        a.stats_ws[r] = st;
-        if (a.stats) a.stats[r] = st;
-        a.mask[r] = i == 0 ? 1 : 0;
-        a.path[r] = -1;
-        if (a.dec) a.dec[r] = 0;
-      }
-      sh_par[i] = static_cast<int16_t>(p);
-      sh_tok[i] = x;
-      sh_zx[i] = zx;
-      sh_qx[i] = qx;
-      if (bad) atomicOr(&sh_bad, bad);
     }
     for (int i = tid; i <= N; i += NT) sh_u[i] = a.u[static_cast<size_t>(b) * (N + 1) + i];
+    merge_rows_coop<NT>(a.partials + rb * a.splits, N, a.splits, a.c, [&](int) { return theta; },
+                        [&](int row, const mars_row_stat& st) {
+                          sh_st[row] = st;
+                          if (g == 0) {
+                            a.stats_ws[rb + row] = st;
+                            if (a.stats) a.stats[rb + row] = st;
+                          }
+                        });
+#pragma unroll
+    for (int t = 0; t < kPerThread; ++t) {
+      const int i = tid + t * NT;
+      if (i < N) { sh_zx[i] = zx[t]; sh_qx[i] = qx[t]; }
+    }
   }
   __syncthreads();
   if (sh_bad != 0) {
