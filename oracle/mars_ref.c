@@ -16,6 +16,12 @@
  *                                                                 the form of the cited speculative-sampling rule)
  *   - token trees verified in one pass                           (Sec. 2.3, tree paragraph)
  *   - bonus token when every draft is accepted, tau <= K+1       (Table 1 caption)
+ *   - the committed sequence V_out: accepted drafts, then the    (Alg. 1, V_out; Sec. 3.4 "standard rollback")
+ *     correction / bonus token; the nodes whose cache rows stay
+ *   - other indicators of a low margin on the same two logits:   (Sec. 3.3: probability ratio P(v2)/P(v1),
+ *     probability ratio, fixed logit margin                       logit margin Delta = z(1) - z(2), Eq. 5-6)
+ *   - distributions of z(1), z(2)/z(1), p2/p1 over rows          (Appendix "Additional Analysis", histogram figure;
+ *                                                                 Sec. 3.3 scatter figure)
  *
  * Readings where the paper is silent (kept identical on purpose in the
  * library's header so both sides state them):
@@ -33,7 +39,15 @@
  *     after each rejection;
  *   - draft_probs == NULL: q is one-hot at the child's token;
  *   - greedy tree: the deepest fully accepted node wins, ties to the lowest
- *     node index; the emitted token is v(1) of that node's row.
+ *     node index; the emitted token is v(1) of that node's row;
+ *   - indicators other than the logit ratio reuse theta[b] as their threshold:
+ *     probability ratio exp(-(z1 - z2)/T') > theta with T' = T, or 1 in greedy
+ *     mode (softmax of the raw logits); fixed margin z1 - z2 < theta.  Neither
+ *     needs the positive-domain condition.  The margin is one rounded fp32
+ *     subtraction on both sides; the probability ratio is evaluated in fp32
+ *     here and the fp64 decision reported beside it (inputs keep a guard band);
+ *   - the cache rows that stay are the root's and the accepted nodes', listed
+ *     request by request in path order as flat row numbers b*N + node.
  *
  * Parity pins: every exported function is pinned by tests/test_oracle_*.py
  * (hand-worked examples, the paper's Fig. 2 ratios, theta > 1 invariants
@@ -54,10 +68,14 @@ typedef struct mars_ref_row {
   double  z1, z2;     /* top-2 logit values, widened exactly */
   double  ratio;      /* z2 / z1 in fp64 (NaN if z1 == 0) */
   double  sum_exp;    /* S = sum_v exp((z_v - z1)/T); 0 when T == 0 */
+  double  prob_ratio; /* P(v2)/P(v1) = exp(-(z1 - z2)/T'), T' = T or 1 when T == 0 */
+  double  gap;        /* Delta = z1 - z2 */
   int32_t id1, id2;
-  int32_t relax_ok;   /* z1 > 0 and fl32(z2/z1) > theta */
-  int32_t relax_ok64; /* same test with the fp64 ratio against (double)theta */
+  int32_t relax_ok;   /* the low-margin test of the chosen indicator, decided in fp32 */
+  int32_t relax_ok64; /* same test decided in fp64 against (double)theta */
 } mars_ref_row;
+
+enum { IND_LOGIT_RATIO = 0, IND_PROB_RATIO = 1, IND_LOGIT_GAP = 2 };
 
 typedef struct mars_ref_diag {
   double  bonus_prob;         /* f(bonus) / sum f for the final distribution */
@@ -93,8 +111,9 @@ static double load_elem(const void* base, int dtype, size_t idx) {
 }
 
 /* Sec. 3.3 / Eq. 4 / Eq. 3 for one row. */
-static void row_stats(const void* logits, int dtype, size_t base, int V, double T,
-                      float theta, mars_ref_row* st) {
+static void row_stats(const void* logits, int dtype, size_t base, int V, float T32,
+                      float theta, int indicator, mars_ref_row* st) {
+  const double T = (double)T32;
   int id1 = 0;
   double z1 = load_elem(logits, dtype, base);
   for (int v = 1; v < V; ++v) {
@@ -110,9 +129,25 @@ static void row_stats(const void* logits, int dtype, size_t base, int V, double 
   }
   st->z1 = z1; st->id1 = id1; st->z2 = z2; st->id2 = id2;
   st->ratio = z2 / z1;
-  float r32 = (float)z2 / (float)z1; /* both casts are exact: the logits are fp32 or bf16 */
-  st->relax_ok = (z1 > 0.0 && r32 > theta) ? 1 : 0;
-  st->relax_ok64 = (z1 > 0.0 && st->ratio > (double)theta) ? 1 : 0;
+  const double Tind = T > 0.0 ? T : 1.0;
+  st->gap = z1 - z2;
+  st->prob_ratio = exp(-(z1 - z2) / Tind);
+  const float z1f = (float)z1, z2f = (float)z2; /* exact: the logits are fp32 or bf16 */
+  if (indicator == IND_LOGIT_RATIO) {        /* Eq. 4 */
+    float r32 = z2f / z1f;
+    st->relax_ok = (z1 > 0.0 && r32 > theta) ? 1 : 0;
+    st->relax_ok64 = (z1 > 0.0 && st->ratio > (double)theta) ? 1 : 0;
+  } else if (indicator == IND_PROB_RATIO) {  /* Sec. 3.3: ratio of the two softmax probabilities */
+    volatile float d32 = z1f - z2f;
+    volatile float x32 = d32 / (T32 > 0.0f ? T32 : 1.0f);
+    float p32 = expf(-x32);
+    st->relax_ok = p32 > theta ? 1 : 0;
+    st->relax_ok64 = st->prob_ratio > (double)theta ? 1 : 0;
+  } else {                                   /* fixed margin on Delta of Eq. 5 */
+    volatile float d32 = z1f - z2f;
+    st->relax_ok = d32 < theta ? 1 : 0;
+    st->relax_ok64 = st->gap < (double)theta ? 1 : 0;
+  }
   double S = 0.0;
   if (T > 0.0) {
     for (int v = 0; v < V; ++v)
@@ -121,17 +156,24 @@ static void row_stats(const void* logits, int dtype, size_t base, int V, double 
   st->sum_exp = S;
 }
 
-int mars_ref_row_stats(const void* logits, int logits_dtype, const float* theta,
-                       float temperature, int B, int N, int V, mars_ref_row* out) {
+int mars_ref_row_stats_ex(const void* logits, int logits_dtype, const float* theta,
+                          float temperature, int indicator, int B, int N, int V,
+                          mars_ref_row* out) {
   if (!logits || !theta || !out || B < 1 || N < 1 || V < 2) return -1;
   if (logits_dtype != REF_F32 && logits_dtype != REF_BF16) return -2;
   if (!(temperature >= 0.0f)) return -1;
+  if (indicator < IND_LOGIT_RATIO || indicator > IND_LOGIT_GAP) return -1;
   long rows = (long)B * N;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(g_threads)
   for (long r = 0; r < rows; ++r)
-    row_stats(logits, logits_dtype, (size_t)r * (size_t)V, V, (double)temperature,
-              theta[r / N], &out[r]);
+    row_stats(logits, logits_dtype, (size_t)r * (size_t)V, V, temperature,
+              theta[r / N], indicator, &out[r]);
   return 0;
+}
+
+int mars_ref_row_stats(const void* logits, int logits_dtype, const float* theta,
+                       float temperature, int B, int N, int V, mars_ref_row* out) {
+  return mars_ref_row_stats_ex(logits, logits_dtype, theta, temperature, IND_LOGIT_RATIO, B, N, V, out);
 }
 
 /* Tree / token validation shared by both modes. */
@@ -271,14 +313,14 @@ static void verify_sampling(const void* logits, int ldt, size_t req_base, int V,
   free(f);
 }
 
-int mars_ref_verify(const void* logits, int logits_dtype,
-                    const int32_t* draft_tokens, const int32_t* tree_parent,
-                    const void* draft_probs, int draft_dtype,
-                    const float* theta, float temperature, const float* uniforms,
-                    int B, int N, int V,
-                    uint8_t* accept_mask, int32_t* accept_len, int32_t* path_idx,
-                    int32_t* bonus_token, uint8_t* decision, int32_t* req_status,
-                    mars_ref_row* stats, mars_ref_diag* diag) {
+int mars_ref_verify_ex(const void* logits, int logits_dtype,
+                       const int32_t* draft_tokens, const int32_t* tree_parent,
+                       const void* draft_probs, int draft_dtype,
+                       const float* theta, float temperature, const float* uniforms,
+                       int B, int N, int V, int indicator,
+                       uint8_t* accept_mask, int32_t* accept_len, int32_t* path_idx,
+                       int32_t* bonus_token, uint8_t* decision, int32_t* req_status,
+                       mars_ref_row* stats, mars_ref_diag* diag) {
   if (!logits || !draft_tokens || !tree_parent || !theta || !accept_mask || !accept_len ||
       !path_idx || !bonus_token)
     return -1;
@@ -290,7 +332,7 @@ int mars_ref_verify(const void* logits, int logits_dtype,
 
   mars_ref_row* st_all = stats;
   if (!st_all) st_all = (mars_ref_row*)malloc((size_t)B * N * sizeof(mars_ref_row));
-  int rc = mars_ref_row_stats(logits, logits_dtype, theta, temperature, B, N, V, st_all);
+  int rc = mars_ref_row_stats_ex(logits, logits_dtype, theta, temperature, indicator, B, N, V, st_all);
   if (rc) { if (!stats) free(st_all); return rc; }
 
 #pragma omp parallel for schedule(dynamic, 1) num_threads(g_threads)
@@ -321,6 +363,114 @@ int mars_ref_verify(const void* logits, int logits_dtype,
                       mask, &accept_len[b], path, &bonus_token[b], dec, dg);
   }
   if (!stats) free(st_all);
+  return 0;
+}
+
+int mars_ref_verify(const void* logits, int logits_dtype,
+                    const int32_t* draft_tokens, const int32_t* tree_parent,
+                    const void* draft_probs, int draft_dtype,
+                    const float* theta, float temperature, const float* uniforms,
+                    int B, int N, int V,
+                    uint8_t* accept_mask, int32_t* accept_len, int32_t* path_idx,
+                    int32_t* bonus_token, uint8_t* decision, int32_t* req_status,
+                    mars_ref_row* stats, mars_ref_diag* diag) {
+  return mars_ref_verify_ex(logits, logits_dtype, draft_tokens, tree_parent, draft_probs, draft_dtype,
+                            theta, temperature, uniforms, B, N, V, IND_LOGIT_RATIO, accept_mask,
+                            accept_len, path_idx, bonus_token, decision, req_status, stats, diag);
+}
+
+/* Alg. 1's V_out and the cache rows that survive (Sec. 3.4, "standard rollback"): per request the
+ * tokens of the accepted nodes in path order followed by the correction / bonus token, and, over
+ * the whole batch, the flat row numbers b*N + node of the root and the accepted nodes. */
+int mars_ref_commit(const int32_t* draft_tokens, const int32_t* accept_len, const int32_t* path_idx,
+                    const int32_t* bonus_token, int B, int N,
+                    int32_t* out_tokens, int32_t* out_len, int32_t* keep_rows, int32_t* keep_offsets) {
+  if (!draft_tokens || !accept_len || !path_idx || !bonus_token || !out_tokens || !out_len ||
+      !keep_rows || !keep_offsets || B < 1 || N < 1)
+    return -1;
+  int total = 0;
+  for (int b = 0; b < B; ++b) {
+    const int32_t* tok = draft_tokens + (size_t)b * N;
+    const int32_t* path = path_idx + (size_t)b * N;
+    int32_t* out = out_tokens + (size_t)b * N;
+    int L = accept_len[b];
+    if (L < 0 || L > N - 1) return -1;
+    keep_offsets[b] = total;
+    keep_rows[total++] = b * N; /* the root's row */
+    for (int j = 0; j < L; ++j) {
+      out[j] = tok[path[j]];
+      keep_rows[total++] = b * N + path[j];
+    }
+    out[L] = bonus_token[b];
+    for (int j = L + 1; j < N; ++j) out[j] = -1;
+    out_len[b] = L + 1;
+  }
+  keep_offsets[B] = total;
+  for (int j = total; j < B * N; ++j) keep_rows[j] = -1;
+  return 0;
+}
+
+/* Distributions of the top-2 statistics over rows (appendix histogram figure: top-1 logit, logit
+ * ratio z2/z1, probability ratio p2/p1; share of negative top-1 logits).
+ *
+ * A histogram over [lo, hi) with `bins` equal cells has bins + 2 counters: [0] counts x < lo,
+ * [bins + 1] counts x >= hi, cell k (0-based) is counter k + 1.  The cell of x is decided in fp32:
+ * trunc(fl(fl(x - lo) * w)), w = fl32(bins / (hi - lo)) from a double division, capped at bins - 1;
+ * x itself is the fp32 value: z1 exactly, fl32(z2 / z1), and the fp32 rounding of the fp64 p2/p1.
+ * Rows with z1 <= 0 have no ratio (Sec. 3.3) and are left out of the ratio histogram.
+ * edge_dist[r] (optional) is the distance, in cells, of row r's p2/p1 from the nearest cell
+ * boundary: p2/p1 goes through an exponential, so a caller comparing against another
+ * implementation can set aside the rows that sit on a boundary. */
+typedef struct mars_ref_margin_row { double z1, z2, ratio, prob_ratio; } mars_ref_margin_row;
+
+static int hist_cell(float x, float lo, float hi, int bins) {
+  if (x < lo) return 0;
+  if (!(x < hi)) return bins + 1;
+  float w = (float)((double)bins / ((double)hi - (double)lo));
+  volatile float d = x - lo;
+  volatile float t = d * w;
+  int k = (int)t;
+  if (k > bins - 1) k = bins - 1;
+  return k + 1;
+}
+
+int mars_ref_margin_stats(const void* logits, int logits_dtype, const float* theta, float temperature,
+                          int B, int N, int V,
+                          const float* range /* 6: lo,hi of z1, ratio, p2/p1 */, const int32_t* bins /* 3 */,
+                          mars_ref_margin_row* rows_out, uint32_t* hist_z1, uint32_t* hist_ratio,
+                          uint32_t* hist_prob, uint32_t* summary /* 4 */, double* edge_dist) {
+  if (!logits || !theta || !range || !bins || !hist_z1 || !hist_ratio || !hist_prob || !summary) return -1;
+  if (B < 1 || N < 1 || V < 2 || !(temperature >= 0.0f)) return -1;
+  for (int h = 0; h < 3; ++h)
+    if (bins[h] < 1 || !(range[2 * h] < range[2 * h + 1])) return -1;
+  long rows = (long)B * N;
+  mars_ref_row* st = (mars_ref_row*)malloc((size_t)rows * sizeof(mars_ref_row));
+  int rc = mars_ref_row_stats(logits, logits_dtype, theta, temperature, B, N, V, st);
+  if (rc) { free(st); return rc; }
+  memset(hist_z1, 0, (size_t)(bins[0] + 2) * sizeof(uint32_t));
+  memset(hist_ratio, 0, (size_t)(bins[1] + 2) * sizeof(uint32_t));
+  memset(hist_prob, 0, (size_t)(bins[2] + 2) * sizeof(uint32_t));
+  uint32_t negative = 0, nonpositive = 0, low_margin = 0;
+  for (long r = 0; r < rows; ++r) {
+    if (rows_out) {
+      rows_out[r].z1 = st[r].z1; rows_out[r].z2 = st[r].z2;
+      rows_out[r].ratio = st[r].ratio; rows_out[r].prob_ratio = st[r].prob_ratio;
+    }
+    float z1f = (float)st[r].z1, z2f = (float)st[r].z2;
+    ++hist_z1[hist_cell(z1f, range[0], range[1], bins[0])];
+    if (st[r].z1 < 0.0) ++negative;
+    if (st[r].z1 <= 0.0) ++nonpositive;
+    else ++hist_ratio[hist_cell(z2f / z1f, range[2], range[3], bins[1])];
+    float pf = (float)st[r].prob_ratio;
+    ++hist_prob[hist_cell(pf, range[4], range[5], bins[2])];
+    if (st[r].relax_ok) ++low_margin;
+    if (edge_dist) {
+      double t = (st[r].prob_ratio - (double)range[4]) * (double)bins[2] / ((double)range[5] - (double)range[4]);
+      edge_dist[r] = fabs(t - nearbyint(t));
+    }
+  }
+  summary[0] = (uint32_t)rows; summary[1] = negative; summary[2] = nonpositive; summary[3] = low_margin;
+  free(st);
   return 0;
 }
 
