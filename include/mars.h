@@ -81,6 +81,18 @@ enum {
 #define MARS_MAX_NODES 1024
 #define MARS_MIN_VOCAB 2
 
+/* Which quantity of the two largest logits decides that a row has a low margin (Sec. 3.3).
+ * All three compare against theta[b], strictly:
+ *   MARS_IND_LOGIT_RATIO  z1 > 0 and fl32(z2/z1) > theta           (Eq. 4; the paper's choice)
+ *   MARS_IND_PROB_RATIO   P(v2)/P(v1) = exp(-(z1 - z2)/T') > theta  with T' = temperature, or 1 in greedy
+ *                         mode (softmax of the raw logits); evaluated in fp32 (about 1 ulp)
+ *   MARS_IND_LOGIT_GAP    fl32(z1 - z2) < theta                     (a fixed margin on Delta of Eq. 5)
+ * Only the logit ratio needs the positive-domain condition. */
+enum { MARS_IND_LOGIT_RATIO = 0, MARS_IND_PROB_RATIO = 1, MARS_IND_LOGIT_GAP = 2 };
+
+/* Most thresholds per request one call of mars_verify_ex sweeps. */
+#define MARS_MAX_THETAS 64
+
 /* Per-row statistics table, one entry per (b, i) row, 24 bytes.
  * z1/z2 are the logit values widened exactly to fp32.  sum_exp is
  * S = sum_v exp((z_v - z1)/T) (Eq. 3 with the max subtracted); 0 in greedy mode. */
@@ -90,7 +102,8 @@ typedef struct mars_row_stat {
   float   z2;
   int32_t id2;
   float   sum_exp;
-  int32_t relax_ok; /* 1 iff z1 > 0 and fl32(z2/z1) > theta[b] */
+  int32_t relax_ok; /* 1 iff the low-margin test holds: z1 > 0 and fl32(z2/z1) > theta[b] (Eq. 4), or the
+                       test of the indicator chosen in mars_verify_ex */
 } mars_row_stat;
 
 /* Optional per-request diagnostics of the sampling-mode walk (floats the
@@ -192,6 +205,95 @@ int mars_verify(const void* logits, int logits_dtype,
                 int32_t* bonus_token, uint8_t* decision, int32_t* request_status,
                 mars_row_stat* stats, mars_req_diag* diag,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Options of mars_verify_ex (a HOST struct; the pointers in it are device pointers).
+ *
+ *   indicator     MARS_IND_*: the low-margin test used for the relaxation (Sec. 3.3 discusses the
+ *                 three; theta[b] is the threshold of whichever is chosen).
+ *   n_theta       K >= 1 (0 is read as 1): thresholds per request.  With K > 1 the call is the
+ *                 threshold ablation of Sec. 4 in one pass over the logits: theta is [K,B], the row
+ *                 reduction runs once, and the per-request part runs for every (k, b) on the same
+ *                 inputs; EVERY output of mars_verify gains a leading axis of length K
+ *                 (accept_mask [K,B,N], accept_len [K,B], ..., stats [K,B*N], diag [K,B]).
+ *   out_tokens    device out, optional, [K,B,N] int32: the committed sequence V_out of Alg. 1 -- the
+ *                 tokens of the accepted nodes in path order, then the correction / bonus token,
+ *                 then -1.
+ *   out_len       device out, [K,B] int32: accept_len + 1.
+ *   keep_rows     device out, [K,B*N] int32: the cache rows that stay after rollback (Sec. 3.4) -- the
+ *                 row b*N + node of the root and of every accepted node, request by request in path
+ *                 order, compacted; then -1.
+ *   keep_offsets  device out, [K,B+1] int32: request b's rows are keep_rows[offsets[b] .. offsets[b+1]).
+ *                 The four are given together or not at all.
+ */
+typedef struct mars_verify_options {
+  int32_t  indicator;
+  int32_t  n_theta;
+  int32_t* out_tokens;
+  int32_t* out_len;
+  int32_t* keep_rows;
+  int32_t* keep_offsets;
+} mars_verify_options;
+
+/* Workspace of mars_verify_ex for a sweep over n_theta thresholds (n_theta = 1: same as
+ * mars_workspace_bytes).  0 if an argument is out of range. */
+size_t mars_workspace_bytes_ex(int B, int N, int V, int n_theta);
+
+/*
+ * mars_verify with options: another low-margin indicator (Sec. 3.3), several thresholds per
+ * request from one read of the logits (the ablation over theta of Sec. 4), and the committed
+ * sequence with the cache rows to keep (Alg. 1, V_out).  Arguments as for mars_verify, with the
+ * shapes stated above when n_theta > 1 and workspace >= mars_workspace_bytes_ex(B,N,V,n_theta);
+ * options == NULL is mars_verify.  n_theta * B requests are verified side by side, which in
+ * sampling mode leaves fewer work-groups per request.  Errors as for mars_verify, plus
+ * MARS_ERR_ARG for an unknown indicator, n_theta outside [0, MARS_MAX_THETAS], or some but not all
+ * of the four commit outputs.
+ */
+int mars_verify_ex(const void* logits, int logits_dtype,
+                   const int32_t* draft_tokens, const int32_t* tree_parent,
+                   const void* draft_probs, int draft_dtype,
+                   const float* theta, float temperature, const float* uniforms,
+                   int B, int N, int V,
+                   uint8_t* accept_mask, int32_t* accept_len, int32_t* path_idx,
+                   int32_t* bonus_token, uint8_t* decision, int32_t* request_status,
+                   mars_row_stat* stats, mars_req_diag* diag,
+                   void* workspace, size_t workspace_bytes, void* hip_stream,
+                   const mars_verify_options* options);
+
+/* One row of mars_margin_stats: the two largest logits, their ratio fl32(z2/z1) (IEEE result also
+ * when z1 <= 0) and the probability ratio P(v2)/P(v1) = exp(-(z1 - z2)/T'), T' as above. */
+typedef struct mars_margin_row {
+  float z1;
+  float z2;
+  float ratio;
+  float prob_ratio;
+} mars_margin_row;
+
+/*
+ * Distributions of the top-2 statistics over all B*N rows, from one pass over the logits: what
+ * the paper's appendix plots to justify theta and the positive-domain assumption (histograms of
+ * the top-1 logit, of z2/z1 and of p2/p1, share of negative top-1 logits), and the share of rows
+ * inside the relaxation zone (Sec. 3.3, scatter figure).
+ *
+ *   theta     device, [B]: threshold of the logit-ratio test counted in the summary.
+ *   range     HOST, 6 floats: lo, hi of the histogram of z1, of z2/z1, of p2/p1 (lo < hi).
+ *   bins      HOST, 3 ints >= 1: cells of each histogram.
+ *   rows_out  device out, optional (NULL ok), [B*N].
+ *   counts    device out, uint32, (bins[0]+2) + (bins[1]+2) + (bins[2]+2) + 4 entries: the three
+ *             histograms one after the other, each as [x < lo | cell 0 .. cell bins-1 | x >= hi],
+ *             then the summary: rows, rows with z1 < 0, rows with z1 <= 0, rows that pass the
+ *             logit-ratio test at theta[b].  The cell of x is trunc(fl32(fl32(x - lo) * w)) with
+ *             w = fl32(bins / (hi - lo)) (the quotient taken in double), capped at bins - 1; x is
+ *             the fp32 value stored in rows_out.  Rows with z1 <= 0 have no ratio and are left out
+ *             of the ratio histogram.
+ *   workspace device, >= mars_workspace_bytes(B,N,V).
+ * Returns MARS_OK or a negative code (MARS_ERR_ARG also for bins < 1, lo >= hi, or more than 2^20
+ * counters); on error nothing is enqueued.
+ */
+int mars_margin_stats(const void* logits, int logits_dtype, const float* theta, float temperature,
+                      int B, int N, int V, const float* range, const int32_t* bins,
+                      mars_margin_row* rows_out, uint32_t* counts,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

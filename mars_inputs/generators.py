@@ -21,6 +21,7 @@ depend on how many threads generate):
 """
 from __future__ import annotations
 
+import math
 import os
 from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
@@ -113,7 +114,20 @@ def _two_largest(row: np.ndarray):
     return float(part[-1]), float(part[-2])
 
 
-def _gen_row(rng, V, background, planted, r_range, theta_b, dtype, guard):
+def _margin_quantity(a: float, b2: float, indicator: str, temperature: float):
+    """The quantity of the two largest stored values that a threshold is compared with (a property of the
+    data, like the ratio): their ratio (None off the positive domain), exp(-(gap)/T'), or their gap."""
+    if indicator == "logit_ratio":
+        return b2 / a if a > 0.0 else None
+    if indicator == "prob_ratio":
+        return math.exp(-(a - b2) / (temperature if temperature > 0 else 1.0))
+    if indicator == "logit_gap":
+        return a - b2
+    raise ValueError(indicator)
+
+
+def _gen_row(rng, V, background, planted, r_range, thetas_b, dtype, guard, indicator="logit_ratio",
+             temperature=0.0):
     while True:
         if background == "normal3":
             z = rng.standard_normal(V, dtype=np.float32) * np.float32(3.0)
@@ -134,8 +148,9 @@ def _gen_row(rng, V, background, planted, r_range, theta_b, dtype, guard):
             bits = None
             stored = z
         a, b2 = _two_largest(stored)
-        if a > 0.0 and abs(b2 / a - float(theta_b)) < guard:
-            continue  # inside the guard band: draw the row again
+        x = _margin_quantity(a, b2, indicator, temperature)
+        if x is not None and any(abs(x - float(t)) < guard for t in thetas_b):
+            continue  # inside the guard band of a threshold: draw the row again
         return stored, bits
 
 
@@ -148,8 +163,8 @@ def _top2_ids(row: np.ndarray):
     return i1, i2
 
 
-def _gen_request(b, *, seed, B, N, V, dtype, background, plant_frac, r_range, theta_b,
-                 tree, sampling, dense_q, guard):
+def _gen_request(b, *, seed, B, N, V, dtype, background, plant_frac, r_range, thetas_b,
+                 tree, sampling, dense_q, guard, indicator, temperature):
     rl = _rng(seed, 1000, b)
     rt = _rng(seed, 2000, b)
     rk = _rng(seed, 3000, b)
@@ -160,7 +175,7 @@ def _gen_request(b, *, seed, B, N, V, dtype, background, plant_frac, r_range, th
     bits = np.empty((N, V), dtype=np.uint16) if dtype == "bf16" else None
     for i in range(N):
         planted = bool(rl.random() < plant_frac)
-        s, bt = _gen_row(rl, V, background, planted, r_range, theta_b, dtype, guard)
+        s, bt = _gen_row(rl, V, background, planted, r_range, thetas_b, dtype, guard, indicator, temperature)
         stored[i] = s
         if bits is not None:
             bits[i] = bt
@@ -207,8 +222,13 @@ def make_workload(name: str, *, B: int, N: int, V: int, dtype: str, temperature:
                   tree: dict, background: str = "normal3", plant_frac: float = 0.4,
                   r_range: Sequence[float] = (0.80, 1.00), theta_choices: Sequence[float] = (0.9,),
                   dense_q: bool = False, seed: int = 0, guard: float = GUARD,
-                  threads: Optional[int] = None) -> Workload:
-    """Generate one workload; every request has its own seeds (seed, stream, b)."""
+                  threads: Optional[int] = None, indicator: str = "logit_ratio",
+                  sweep_thetas: Sequence[float] = ()) -> Workload:
+    """Generate one workload; every request has its own seeds (seed, stream, b).
+
+    ``indicator`` names the quantity the thresholds are compared with (logit_ratio, prob_ratio, logit_gap):
+    the guard band around theta is kept on that quantity.  ``sweep_thetas`` are further thresholds (of a
+    sweep over theta) every row also keeps clear of."""
     assert dtype in ("f32", "bf16")
     sampling = temperature > 0
     rth = _rng(seed, 6000, 0)
@@ -216,10 +236,12 @@ def make_workload(name: str, *, B: int, N: int, V: int, dtype: str, temperature:
     if threads is None:
         threads = min(16, os.cpu_count() or 1, B)
     kw = dict(seed=seed, B=B, N=N, V=V, dtype=dtype, background=background, plant_frac=plant_frac,
-              r_range=tuple(r_range), tree=tree, sampling=sampling, dense_q=dense_q, guard=guard)
+              r_range=tuple(r_range), tree=tree, sampling=sampling, dense_q=dense_q, guard=guard,
+              indicator=indicator, temperature=float(np.float32(temperature)))
+    sweep = [float(np.float32(t)) for t in sweep_thetas]
 
     def job(b):
-        return _gen_request(b, theta_b=float(theta[b]), **kw)
+        return _gen_request(b, thetas_b=[float(theta[b])] + sweep, **kw)
 
     if threads > 1:
         with ThreadPoolExecutor(max_workers=threads) as ex:
@@ -246,7 +268,8 @@ def make_workload(name: str, *, B: int, N: int, V: int, dtype: str, temperature:
                     theta=theta, logits=logits, draft_tokens=tokens, tree_parent=parents,
                     uniforms=uniforms, draft_probs=dprobs,
                     meta=dict(seed=seed, tree=tree, background=background, plant_frac=plant_frac,
-                              r_range=tuple(r_range), dense_q=dense_q, guard=guard))
+                              r_range=tuple(r_range), dense_q=dense_q, guard=guard, indicator=indicator,
+                              sweep_thetas=tuple(sweep)))
 
 
 # --------------------------------------------------------------------------- the five stated configurations

@@ -30,30 +30,45 @@ def _sub(a, idx):
 
 
 def screen_uniforms(w, guard: float = 1e-4, min_norm: float = 2e-2, max_rounds: int = 200,
-                    seed: int = 987654321, cdf_guard: float = None):
+                    seed: int = 987654321, cdf_guard: float = None, indicator: int = 0, thetas=None):
     """``w`` is a workload object with numpy fields (logits, draft_tokens, tree_parent, theta,
-    temperature, uniforms, draft_probs); ``w.uniforms`` is updated in place."""
-    out = mars_ref.verify(w.logits, w.draft_tokens, w.tree_parent, w.theta, w.temperature,
-                          w.uniforms, w.draft_probs)
+    temperature, uniforms, draft_probs); ``w.uniforms`` is updated in place.
+
+    ``thetas`` [K,B] (optional) screens for a sweep: the same uniforms serve the K walks of a
+    request, so a request is re-drawn until all K of them are clean; the outputs then carry a
+    leading axis of length K."""
+    th = np.asarray(w.theta, np.float32)[None] if thetas is None else np.asarray(thetas, np.float32)
+    K = th.shape[0]
+
+    def run(idx=None):
+        pick = (lambda a: a) if idx is None else (lambda a: _sub(a, idx))
+        return [mars_ref.verify(pick(w.logits), pick(w.draft_tokens), pick(w.tree_parent),
+                                th[k] if idx is None else th[k][idx], w.temperature, pick(w.uniforms),
+                                pick(w.draft_probs), indicator) for k in range(K)]
+
+    def result(outs):
+        return outs[0] if thetas is None else {key: np.stack([o[key] for o in outs]) for key in outs[0]}
+
+    outs = run()
     if not w.temperature > 0:
-        return out
+        return result(outs)
     if cdf_guard is None:
         cdf_guard = guard
     rounds = 0
     while True:
-        d = out["diag"]
-        bad = np.nonzero((d["min_accept_margin"] < guard) | (d["min_cdf_margin"] < cdf_guard)
-                         | (d["min_norm"] < min_norm))[0]
+        dirty = np.zeros(w.uniforms.shape[0], bool)
+        for o in outs:
+            d = o["diag"]
+            dirty |= (d["min_accept_margin"] < guard) | (d["min_cdf_margin"] < cdf_guard) | (d["min_norm"] < min_norm)
+        bad = np.nonzero(dirty)[0]
         if bad.size == 0:
-            return out
+            return result(outs)
         rounds += 1
         if rounds > max_rounds:
             raise RuntimeError(f"uniform guard band not reached for requests {bad.tolist()}")
         for b in bad:
             rng = np.random.default_rng(np.random.SeedSequence([seed, rounds, int(b)]))
             w.uniforms[b] = rng.random(w.uniforms.shape[1], dtype=np.float32)
-        sub = mars_ref.verify(_sub(w.logits, bad), _sub(w.draft_tokens, bad), _sub(w.tree_parent, bad),
-                              _sub(w.theta, bad), w.temperature, _sub(w.uniforms, bad),
-                              _sub(w.draft_probs, bad))
-        for k, v in sub.items():
-            out[k][bad] = v
+        for o, sub in zip(outs, run(bad)):
+            for k, v in sub.items():
+                o[k][bad] = v

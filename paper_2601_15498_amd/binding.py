@@ -16,6 +16,15 @@ LIB_PATH = os.path.join(_HERE, "libmars.so")
 MARS_F32, MARS_BF16 = 0, 1
 MARS_OK = 0
 MARS_MAX_NODES = 1024
+MARS_MAX_THETAS = 64
+MARS_IND_LOGIT_RATIO, MARS_IND_PROB_RATIO, MARS_IND_LOGIT_GAP = 0, 1, 2
+
+
+class VerifyOptionsStruct(ctypes.Structure):
+    """struct mars_verify_options (a host struct holding device pointers)."""
+    _fields_ = [("indicator", ctypes.c_int32), ("n_theta", ctypes.c_int32),
+                ("out_tokens", ctypes.c_void_p), ("out_len", ctypes.c_void_p),
+                ("keep_rows", ctypes.c_void_p), ("keep_offsets", ctypes.c_void_p)]
 
 _lib = None
 
@@ -49,6 +58,16 @@ def lib():
                                    ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_float,
                                    ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
                                   + [ctypes.c_void_p] * 8 + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p])
+        L.mars_workspace_bytes_ex.restype = ctypes.c_size_t
+        L.mars_workspace_bytes_ex.argtypes = [ctypes.c_int] * 4
+        L.mars_verify_ex.restype = ctypes.c_int
+        L.mars_verify_ex.argtypes = L.mars_verify.argtypes + [ctypes.POINTER(VerifyOptionsStruct)]
+        L.mars_margin_stats.restype = ctypes.c_int
+        L.mars_margin_stats.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_float,
+                                        ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                        ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32),
+                                        ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -88,10 +107,14 @@ def mars_workspace_bytes(B: int, N: int, V: int) -> int:
     return int(lib().mars_workspace_bytes(B, N, V))
 
 
-def alloc_workspace(B: int, N: int, V: int, device="cuda") -> torch.Tensor:
-    n = mars_workspace_bytes(B, N, V)
+def mars_workspace_bytes_ex(B: int, N: int, V: int, n_theta: int) -> int:
+    return int(lib().mars_workspace_bytes_ex(B, N, V, n_theta))
+
+
+def alloc_workspace(B: int, N: int, V: int, device="cuda", n_theta: int = 1) -> torch.Tensor:
+    n = mars_workspace_bytes_ex(B, N, V, n_theta)
     if n == 0:
-        raise MarsError(f"sizes out of range: B={B} N={N} V={V}")
+        raise MarsError(f"sizes out of range: B={B} N={N} V={V} n_theta={n_theta}")
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
@@ -130,17 +153,28 @@ def unpack_diag(diag: torch.Tensor) -> dict:
 
 
 class VerifyOutputs:
-    """Device tensors written by ``mars_verify``."""
+    """Device tensors written by ``mars_verify`` / ``mars_verify_ex``.  With n_theta = K > 1 every tensor
+    has a leading axis of length K; with want_commit the committed sequence and kept cache rows too."""
 
-    def __init__(self, B: int, N: int, device, want_stats: bool = True, want_diag: bool = True):
-        self.accept_mask = torch.empty((B, N), dtype=torch.uint8, device=device)
-        self.accept_len = torch.empty((B,), dtype=torch.int32, device=device)
-        self.path_idx = torch.empty((B, N), dtype=torch.int32, device=device)
-        self.bonus_token = torch.empty((B,), dtype=torch.int32, device=device)
-        self.decision = torch.empty((B, N), dtype=torch.uint8, device=device)
-        self.request_status = torch.empty((B,), dtype=torch.int32, device=device)
-        self.stats = torch.empty((B * N, ROW_STAT_WORDS), dtype=torch.int32, device=device) if want_stats else None
-        self.diag = torch.empty((B, REQ_DIAG_WORDS), dtype=torch.int32, device=device) if want_diag else None
+    def __init__(self, B: int, N: int, device, want_stats: bool = True, want_diag: bool = True,
+                 n_theta: int = 1, want_commit: bool = False):
+        lead = (n_theta,) if n_theta > 1 else ()
+        self.n_theta = n_theta
+        self.accept_mask = torch.empty(lead + (B, N), dtype=torch.uint8, device=device)
+        self.accept_len = torch.empty(lead + (B,), dtype=torch.int32, device=device)
+        self.path_idx = torch.empty(lead + (B, N), dtype=torch.int32, device=device)
+        self.bonus_token = torch.empty(lead + (B,), dtype=torch.int32, device=device)
+        self.decision = torch.empty(lead + (B, N), dtype=torch.uint8, device=device)
+        self.request_status = torch.empty(lead + (B,), dtype=torch.int32, device=device)
+        self.stats = (torch.empty(lead + (B * N, ROW_STAT_WORDS), dtype=torch.int32, device=device)
+                      if want_stats else None)
+        self.diag = torch.empty(lead + (B, REQ_DIAG_WORDS), dtype=torch.int32, device=device) if want_diag else None
+        self.out_tokens = self.out_len = self.keep_rows = self.keep_offsets = None
+        if want_commit:
+            self.out_tokens = torch.empty(lead + (B, N), dtype=torch.int32, device=device)
+            self.out_len = torch.empty(lead + (B,), dtype=torch.int32, device=device)
+            self.keep_rows = torch.empty(lead + (B * N,), dtype=torch.int32, device=device)
+            self.keep_offsets = torch.empty(lead + (B + 1,), dtype=torch.int32, device=device)
 
 
 def mars_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: torch.Tensor,
@@ -170,3 +204,72 @@ def mars_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: t
                              _ptr(out.bonus_token), _ptr(out.decision), _ptr(out.request_status),
                              _ptr(out.stats), _ptr(out.diag), _ptr(workspace), workspace.numel(), _stream()))
     return out
+
+
+def mars_verify_ex(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: torch.Tensor,
+                   theta: torch.Tensor, temperature: float, uniforms: torch.Tensor = None,
+                   draft_probs: torch.Tensor = None, out: VerifyOutputs = None, workspace: torch.Tensor = None,
+                   indicator: int = MARS_IND_LOGIT_RATIO, n_theta: int = 1,
+                   want_commit: bool = False) -> VerifyOutputs:
+    """mars_verify with options: low-margin indicator, theta[K,B] swept in one pass, committed sequence and
+    kept cache rows.  See include/mars.h."""
+    B, N, V = logits.shape
+    dev = logits.device
+    assert logits.is_contiguous()
+    assert draft_tokens.dtype == torch.int32 and draft_tokens.shape == (B, N) and draft_tokens.is_contiguous()
+    assert tree_parent.dtype == torch.int32 and tree_parent.shape == (B, N) and tree_parent.is_contiguous()
+    assert theta.dtype == torch.float32 and theta.numel() == n_theta * B and theta.is_contiguous()
+    if uniforms is not None:
+        assert uniforms.dtype == torch.float32 and uniforms.shape == (B, N + 1) and uniforms.is_contiguous()
+    dcode = 0
+    if draft_probs is not None:
+        assert draft_probs.shape == (B, N, V) and draft_probs.is_contiguous()
+        dcode = _dtype_code(draft_probs)
+    if out is None:
+        out = VerifyOutputs(B, N, dev, n_theta=n_theta, want_commit=want_commit)
+    assert out.n_theta == n_theta
+    if workspace is None:
+        workspace = alloc_workspace(B, N, V, dev, n_theta)
+    opt = VerifyOptionsStruct(int(indicator), int(n_theta),
+                              None if out.out_tokens is None else out.out_tokens.data_ptr(),
+                              None if out.out_len is None else out.out_len.data_ptr(),
+                              None if out.keep_rows is None else out.keep_rows.data_ptr(),
+                              None if out.keep_offsets is None else out.keep_offsets.data_ptr())
+    _check(lib().mars_verify_ex(_ptr(logits), _dtype_code(logits), _ptr(draft_tokens), _ptr(tree_parent),
+                                _ptr(draft_probs), dcode, _ptr(theta), float(temperature), _ptr(uniforms),
+                                B, N, V, _ptr(out.accept_mask), _ptr(out.accept_len), _ptr(out.path_idx),
+                                _ptr(out.bonus_token), _ptr(out.decision), _ptr(out.request_status),
+                                _ptr(out.stats), _ptr(out.diag), _ptr(workspace), workspace.numel(), _stream(),
+                                ctypes.byref(opt)))
+    return out
+
+
+# struct mars_margin_row {float z1; float z2; float ratio; float prob_ratio;}
+MARGIN_ROW_WORDS = 4
+
+
+def margin_counts_len(bins) -> int:
+    return sum(int(b) + 2 for b in bins) + 4
+
+
+def mars_margin_stats(logits: torch.Tensor, theta: torch.Tensor, temperature: float, ranges, bins,
+                      rows_out: torch.Tensor = None, counts: torch.Tensor = None, workspace: torch.Tensor = None,
+                      want_rows: bool = True):
+    """Top-2 statistics per row ([B*N, 4] fp32: z1, z2, z2/z1, p2/p1) and their histograms (one uint32 tensor:
+    three histograms of bins+2 counters each, then rows, z1 < 0, z1 <= 0, low-margin rows).  ranges: six floats
+    (lo, hi of z1, of z2/z1, of p2/p1); bins: three ints.  See include/mars.h."""
+    B, N, V = logits.shape
+    dev = logits.device
+    assert logits.is_contiguous() and theta.dtype == torch.float32 and theta.numel() == B
+    rg = (ctypes.c_float * 6)(*[float(x) for x in ranges])
+    bn = (ctypes.c_int32 * 3)(*[int(x) for x in bins])
+    if rows_out is None and want_rows:
+        rows_out = torch.empty((B * N, MARGIN_ROW_WORDS), dtype=torch.float32, device=dev)
+    if counts is None:
+        counts = torch.empty((margin_counts_len(bins),), dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = alloc_workspace(B, N, V, dev)
+    _check(lib().mars_margin_stats(_ptr(logits), _dtype_code(logits), _ptr(theta), float(temperature), B, N, V,
+                                   rg, bn, _ptr(rows_out), _ptr(counts), _ptr(workspace), workspace.numel(),
+                                   _stream()))
+    return rows_out, counts

@@ -176,12 +176,40 @@ struct Partial {
   float   ref;
 };
 
+// 2^x for a double argument, to fp32 accuracy whatever the magnitude of x: the integer part is
+// applied exactly, the fraction in [-1/2, 1/2] goes through one fp32 exp2.
+__device__ __forceinline__ float exp2_split(double x) {
+  if (!(x > -400.0)) return 0.0f;
+  const double n = rint(x);
+  const float frac = static_cast<float>(x - n);
+  return static_cast<float>(ldexp(static_cast<double>(__builtin_amdgcn_exp2f(frac)), static_cast<int>(n)));
+}
+
+// The low-margin test on the two largest logits of a row (Sec. 3.3), strict, against the
+// request's threshold.  cind = log2(e) / T' with T' the sampling temperature, or 1 in greedy mode.
+//   logit ratio (Eq. 4):  z1 > 0 and z2/z1 > theta, one correctly rounded fp32 division; no
+//                         relaxation outside the positive domain the paper assumes for z(1)
+//   probability ratio:    P(v2)/P(v1) = exp(-(z1 - z2)/T') > theta
+//   fixed margin:         Delta = z1 - z2 < theta (Delta of Eq. 5, one rounded fp32 subtraction)
+struct Indicator {
+  int kind;      // mars_indicator
+  double cind;
+};
+__device__ __forceinline__ float prob_ratio(float z1, float z2, double cind) {
+  return exp2_split(-static_cast<double>(__fsub_rn(z1, z2)) * cind);
+}
+__device__ __forceinline__ int low_margin(float z1, float z2, float theta, const Indicator& ind) {
+  if (ind.kind == MARS_IND_PROB_RATIO) return prob_ratio(z1, z2, ind.cind) > theta ? 1 : 0;
+  if (ind.kind == MARS_IND_LOGIT_GAP) return __fsub_rn(z1, z2) < theta ? 1 : 0;
+  return (z1 > 0.0f && (z2 / z1) > theta) ? 1 : 0;
+}
+
 // Finish one row: the merged keys and the sum S (relative to the integer reference R) become
 // the public statistics entry.  Moving the reference to the row maximum needs the only
 // exponential of the merge, of an argument split into its integer part (exact) and a
 // fraction in [-1/2, 1/2] (one fp32 exp2).
 __device__ __forceinline__ mars_row_stat finish_row(unsigned long long k1, unsigned long long k2, float R, double S,
-                                                    float theta, float c) {
+                                                    float theta, float c, const Indicator& ind) {
   const float z1 = key_value(k1), z2 = key_value(k2);
   float sum_exp = 0.0f;
   if (c > 0.0f && S > 0.0) {
@@ -195,9 +223,7 @@ __device__ __forceinline__ mars_row_stat finish_row(unsigned long long k1, unsig
   st.z1 = z1; st.id1 = key_index(k1);
   st.z2 = z2; st.id2 = key_index(k2);
   st.sum_exp = sum_exp;
-  // Eq. 4 and the strict test r > theta, one correctly rounded fp32 division; no
-  // relaxation outside the positive domain the paper assumes for z(1).
-  st.relax_ok = (z1 > 0.0f && (z2 / z1) > theta) ? 1 : 0;
+  st.relax_ok = low_margin(z1, z2, theta, ind);
   return st;
 }
 
@@ -225,7 +251,7 @@ __device__ __forceinline__ unsigned long long dpp_move(unsigned long long v) {
 // Must be called by all NT threads of the work-group (NT a multiple of 64).
 template <int NT, typename ThetaAt, typename Emit>
 __device__ __forceinline__ void merge_rows_coop(const Partial* __restrict__ partials, int nrows, int parts,
-                                                float c, ThetaAt theta_at, Emit emit) {
+                                                float c, const Indicator& ind, ThetaAt theta_at, Emit emit) {
   const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
   constexpr int kGroups = NT / 16;
   for (int row0 = 0; row0 < nrows; row0 += kGroups) {
@@ -259,7 +285,7 @@ __device__ __forceinline__ void merge_rows_coop(const Partial* __restrict__ part
     MARS_MERGE_STEP(kDppHalfMirror)
     MARS_MERGE_STEP(kDppMirror)
 #undef MARS_MERGE_STEP
-    if (live && sub == 0) emit(row, finish_row(k1, k2, R, S, theta_at(row), c));
+    if (live && sub == 0) emit(row, finish_row(k1, k2, R, S, theta_at(row), c, ind));
   }
 }
 

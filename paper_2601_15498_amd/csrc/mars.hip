@@ -51,54 +51,70 @@ static int choose_groups(int B, int V) {
   return G;
 }
 
-static Layout layout(int B, int N, int V) {
+// K = thresholds per request: the row reduction works on the B*N rows once, the per-request
+// part on K*B requests (statistics table and exchange words per (threshold, request)).
+static Layout layout(int B, int N, int V, int K = 1) {
   Layout L;
   const long rows = static_cast<long>(B) * N;
   L.splits = choose_splits(rows, V);
   L.partials_off = 0;
   L.stats_off = align_up(static_cast<size_t>(rows) * L.splits * kPartsPerItem * sizeof(Partial));
-  L.G = choose_groups(B, V);
-  L.xslots_off = L.stats_off + align_up(static_cast<size_t>(rows) * sizeof(mars_row_stat));
-  L.total = L.xslots_off + align_up(static_cast<size_t>(B) * (N + 2) * 2 * L.G * sizeof(unsigned long long));
+  L.G = choose_groups(K * B, V);
+  L.xslots_off = L.stats_off + align_up(static_cast<size_t>(K) * rows * sizeof(mars_row_stat));
+  L.total = L.xslots_off +
+            align_up(static_cast<size_t>(K) * B * (N + 2) * 2 * L.G * sizeof(unsigned long long));
   return L;
 }
 
-static bool sizes_ok(int B, int N, int V) {
-  if (B < 1 || N < 1 || N > MARS_MAX_NODES || V < MARS_MIN_VOCAB) return false;
-  const long rows = static_cast<long>(B) * N;
+static bool sizes_ok(int B, int N, int V, int K = 1) {
+  if (B < 1 || N < 1 || N > MARS_MAX_NODES || V < MARS_MIN_VOCAB || K < 1 || K > MARS_MAX_THETAS) return false;
+  const long rows = static_cast<long>(B) * N * K;
   return rows <= 0x7FFFFFFFL / 64;  // rows * splits must fit the grid and int arithmetic
 }
 
 template <typename T, int EPV>
 static hipError_t launch_row_reduce_t(const void* logits, long rows, int V, int splits, bool sampling, float c,
-                                      Partial* partials, unsigned long long* xslots, int N, int xwords, hipStream_t stream) {
+                                      Partial* partials, const ClearArgs& clr, hipStream_t stream) {
   const int nvec = V / EPV;
   const int vps = (nvec + splits - 1) / splits;
   const dim3 grid(static_cast<unsigned int>(rows * splits)), block(kRowThreads);
   if (sampling)
     hipLaunchKernelGGL((row_reduce_kernel<T, EPV, true>), grid, block, 0, stream, static_cast<const T*>(logits), V,
-                       splits, vps, c, partials, xslots, N, xwords);
+                       splits, vps, c, partials, clr);
   else
     hipLaunchKernelGGL((row_reduce_kernel<T, EPV, false>), grid, block, 0, stream, static_cast<const T*>(logits), V,
-                       splits, vps, c, partials, xslots, N, xwords);
+                       splits, vps, c, partials, clr);
   return hipGetLastError();
 }
 
 // 16-byte loads need every row to start on a 16-byte boundary; otherwise the same kernel runs
 // with one element per load.
 static hipError_t launch_row_reduce(const void* logits, int dtype, long rows, int V, int splits, bool sampling,
-                                    float c, Partial* partials, unsigned long long* xslots, int N, int xwords, hipStream_t stream) {
+                                    float c, Partial* partials, const ClearArgs& clr, hipStream_t stream) {
   const size_t elt = dtype == MARS_BF16 ? 2 : 4;
   const bool wide = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && ((static_cast<size_t>(V) * elt) % 16 == 0);
   if (dtype == MARS_BF16)
-    return wide ? launch_row_reduce_t<bf16_t, 8>(logits, rows, V, splits, sampling, c, partials, xslots, N, xwords, stream)
-                : launch_row_reduce_t<bf16_t, 1>(logits, rows, V, splits, sampling, c, partials, xslots, N, xwords, stream);
-  return wide ? launch_row_reduce_t<float, 4>(logits, rows, V, splits, sampling, c, partials, xslots, N, xwords, stream)
-              : launch_row_reduce_t<float, 1>(logits, rows, V, splits, sampling, c, partials, xslots, N, xwords, stream);
+    return wide ? launch_row_reduce_t<bf16_t, 8>(logits, rows, V, splits, sampling, c, partials, clr, stream)
+                : launch_row_reduce_t<bf16_t, 1>(logits, rows, V, splits, sampling, c, partials, clr, stream);
+  return wide ? launch_row_reduce_t<float, 4>(logits, rows, V, splits, sampling, c, partials, clr, stream)
+              : launch_row_reduce_t<float, 1>(logits, rows, V, splits, sampling, c, partials, clr, stream);
 }
 
 static float log2e_over_t(float temperature) {
   return temperature > 0.0f ? static_cast<float>(1.4426950408889634 / static_cast<double>(temperature)) : 0.0f;
+}
+
+// log2(e) / T' for the probability-ratio indicator: T' is the sampling temperature, 1 in greedy mode.
+static double indicator_scale(float temperature) {
+  return 1.4426950408889634 / (temperature > 0.0f ? static_cast<double>(temperature) : 1.0);
+}
+
+static ClearArgs clear_args(char* ws, const Layout& L, int B, int N, int K) {
+  ClearArgs clr;
+  clr.xslots = reinterpret_cast<unsigned long long*>(ws + L.xslots_off);
+  clr.N = N; clr.B = B; clr.xwords = 2 * L.G; clr.copies = K;
+  clr.counters = nullptr; clr.ncounters = 0;
+  return clr;
 }
 
 }  // namespace mars
@@ -134,9 +150,9 @@ int mars_row_reduce(const void* logits, int logits_dtype, float temperature, int
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0 || workspace_bytes < L.total)
     return MARS_ERR_WORKSPACE;
   Partial* partials = reinterpret_cast<Partial*>(static_cast<char*>(workspace) + L.partials_off);
-  unsigned long long* xslots = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + L.xslots_off);
   const hipError_t e = launch_row_reduce(logits, logits_dtype, static_cast<long>(B) * N, V, L.splits,
-                                         temperature > 0.0f, log2e_over_t(temperature), partials, xslots, N, 2 * L.G,
+                                         temperature > 0.0f, log2e_over_t(temperature), partials,
+                                         clear_args(static_cast<char*>(workspace), L, B, N, 1),
                                          static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? MARS_OK : MARS_ERR_HIP;
 }
@@ -155,14 +171,20 @@ int mars_row_stats(const void* logits, int logits_dtype, const float* theta, flo
   const long rows = static_cast<long>(B) * N;
   Partial* partials = reinterpret_cast<Partial*>(static_cast<char*>(workspace) + L.partials_off);
   const float c = log2e_over_t(temperature);
-  unsigned long long* xslots = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + L.xslots_off);
-  if (launch_row_reduce(logits, logits_dtype, rows, V, L.splits, temperature > 0.0f, c, partials, xslots, N, 2 * L.G,
-                        stream) != hipSuccess)
+  if (launch_row_reduce(logits, logits_dtype, rows, V, L.splits, temperature > 0.0f, c, partials,
+                        clear_args(static_cast<char*>(workspace), L, B, N, 1), stream) != hipSuccess)
     return MARS_ERR_HIP;
   const int threads = 256, rows_per_group = 16;
+  const Indicator ind = {MARS_IND_LOGIT_RATIO, indicator_scale(temperature)};
   hipLaunchKernelGGL(merge_stats_kernel, dim3(static_cast<unsigned int>((rows + rows_per_group - 1) / rows_per_group)),
-                     dim3(threads), 0, stream, partials, static_cast<int>(rows), N, L.splits * kPartsPerItem, theta, c, stats);
+                     dim3(threads), 0, stream, partials, static_cast<int>(rows), N, L.splits * kPartsPerItem, theta, c,
+                     ind, stats);
   return hipGetLastError() == hipSuccess ? MARS_OK : MARS_ERR_HIP;
+}
+
+size_t mars_workspace_bytes_ex(int B, int N, int V, int n_theta) {
+  if (!mars::sizes_ok(B, N, V, n_theta)) return 0;
+  return mars::layout(B, N, V, n_theta).total;
 }
 
 int mars_verify(const void* logits, int logits_dtype, const int32_t* draft_tokens, const int32_t* tree_parent,
@@ -171,17 +193,40 @@ int mars_verify(const void* logits, int logits_dtype, const int32_t* draft_token
                 int32_t* path_idx, int32_t* bonus_token, uint8_t* decision, int32_t* request_status,
                 mars_row_stat* stats, mars_req_diag* diag, void* workspace, size_t workspace_bytes,
                 void* hip_stream) {
+  return mars_verify_ex(logits, logits_dtype, draft_tokens, tree_parent, draft_probs, draft_dtype, theta, temperature,
+                        uniforms, B, N, V, accept_mask, accept_len, path_idx, bonus_token, decision, request_status,
+                        stats, diag, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_tokens, const int32_t* tree_parent,
+                   const void* draft_probs, int draft_dtype, const float* theta, float temperature,
+                   const float* uniforms, int B, int N, int V, uint8_t* accept_mask, int32_t* accept_len,
+                   int32_t* path_idx, int32_t* bonus_token, uint8_t* decision, int32_t* request_status,
+                   mars_row_stat* stats, mars_req_diag* diag, void* workspace, size_t workspace_bytes,
+                   void* hip_stream, const mars_verify_options* options) {
   using namespace mars;
   if (!logits || !draft_tokens || !tree_parent || !theta || !accept_mask || !accept_len || !path_idx || !bonus_token)
     return MARS_ERR_ARG;
-  if (!sizes_ok(B, N, V)) return MARS_ERR_ARG;
+  int K = 1, indicator = MARS_IND_LOGIT_RATIO;
+  int32_t *out_tokens = nullptr, *out_len = nullptr, *keep_rows = nullptr, *keep_offsets = nullptr;
+  if (options) {
+    K = options->n_theta == 0 ? 1 : options->n_theta;
+    indicator = options->indicator;
+    out_tokens = options->out_tokens; out_len = options->out_len;
+    keep_rows = options->keep_rows; keep_offsets = options->keep_offsets;
+  }
+  if (indicator != MARS_IND_LOGIT_RATIO && indicator != MARS_IND_PROB_RATIO && indicator != MARS_IND_LOGIT_GAP)
+    return MARS_ERR_ARG;
+  const int given = (out_tokens != nullptr) + (out_len != nullptr) + (keep_rows != nullptr) + (keep_offsets != nullptr);
+  if (given != 0 && given != 4) return MARS_ERR_ARG;
+  if (!sizes_ok(B, N, V, K)) return MARS_ERR_ARG;
   if (!(temperature >= 0.0f) || std::isinf(temperature)) return MARS_ERR_ARG;
   const bool sampling = temperature > 0.0f;
   if (sampling && !uniforms) return MARS_ERR_ARG;
   if (logits_dtype != MARS_F32 && logits_dtype != MARS_BF16) return MARS_ERR_DTYPE;
   const bool dense = sampling && draft_probs != nullptr;
   if (dense && draft_dtype != MARS_F32 && draft_dtype != MARS_BF16) return MARS_ERR_DTYPE;
-  const Layout L = layout(B, N, V);
+  const Layout L = layout(B, N, V, K);
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0 || workspace_bytes < L.total)
     return MARS_ERR_WORKSPACE;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -190,9 +235,8 @@ int mars_verify(const void* logits, int logits_dtype, const int32_t* draft_token
   Partial* partials = reinterpret_cast<Partial*>(ws + L.partials_off);
   const float c = log2e_over_t(temperature);
 
-  unsigned long long* xslots = reinterpret_cast<unsigned long long*>(ws + L.xslots_off);
-  if (launch_row_reduce(logits, logits_dtype, rows, V, L.splits, sampling, c, partials, xslots, N, 2 * L.G, stream) !=
-      hipSuccess)
+  const ClearArgs clr = clear_args(ws, L, B, N, K);
+  if (launch_row_reduce(logits, logits_dtype, rows, V, L.splits, sampling, c, partials, clr, stream) != hipSuccess)
     return MARS_ERR_HIP;
 
   TailArgs a;
@@ -203,14 +247,25 @@ int mars_verify(const void* logits, int logits_dtype, const int32_t* draft_token
   a.stats_ws = reinterpret_cast<mars_row_stat*>(ws + L.stats_off);
   a.G = sampling ? L.G : 1;
   a.spin_limit = 1 << 20;  // on the order of a second of polling before a request gives up on its partners
-  a.xslots = xslots;
+  a.xslots = clr.xslots;
   a.mask = accept_mask; a.len = accept_len; a.path = path_idx; a.bonus = bonus_token;
   a.dec = decision; a.status = request_status; a.diag = diag;
-  a.B = B; a.N = N; a.V = V; a.splits = L.splits * kPartsPerItem; a.c = c;
+  a.B = K * B; a.Bd = B; a.N = N; a.V = V; a.splits = L.splits * kPartsPerItem; a.c = c;
+  a.ind.kind = indicator; a.ind.cind = indicator_scale(temperature);
+  a.out_tok = out_tokens; a.out_len = out_len;
+
+  // The cache rows that stay: a small kernel behind the walk (one work-group per threshold).
+  auto finish = [&]() -> int {
+    if (hipGetLastError() != hipSuccess) return MARS_ERR_HIP;
+    if (!keep_rows) return MARS_OK;
+    hipLaunchKernelGGL(compact_keep_kernel, dim3(static_cast<unsigned int>(K)), dim3(kKeepThreads), 0, stream,
+                       out_len, path_idx, B, N, keep_rows, keep_offsets);
+    return hipGetLastError() == hipSuccess ? MARS_OK : MARS_ERR_HIP;
+  };
 
   if (!sampling) {
-    hipLaunchKernelGGL(tail_greedy_kernel, dim3(static_cast<unsigned int>(B)), dim3(kGreedyThreads), 0, stream, a);
-    return hipGetLastError() == hipSuccess ? MARS_OK : MARS_ERR_HIP;
+    hipLaunchKernelGGL(tail_greedy_kernel, dim3(static_cast<unsigned int>(K * B)), dim3(kGreedyThreads), 0, stream, a);
+    return finish();
   }
   // Slices of at most kResident groups of eight per thread stay in registers between passes.
   const int ngroups8 = (V + 7) / 8;
@@ -230,10 +285,46 @@ int mars_verify(const void* logits, int logits_dtype, const int32_t* draft_token
   // The waits are bounded: should foreign work keep part of the grid from being scheduled, the
   // affected requests end with MARS_REQ_TIMEOUT instead of hanging.  (A cooperative launch
   // would have the runtime check residency, at the price of ~20 us per call on this stack.)
-  if (hipLaunchKernel(kernel, dim3(static_cast<unsigned int>(B) * a.G), dim3(kSamplingThreads), params, 0,
+  if (hipLaunchKernel(kernel, dim3(static_cast<unsigned int>(K * B) * a.G), dim3(kSamplingThreads), params, 0,
                       stream) !=
       hipSuccess)
     return MARS_ERR_HIP;
+  return finish();
+}
+
+int mars_margin_stats(const void* logits, int logits_dtype, const float* theta, float temperature, int B, int N, int V,
+                      const float* range, const int32_t* bins, mars_margin_row* rows_out, uint32_t* counts,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  using namespace mars;
+  if (!logits || !theta || !range || !bins || !counts) return MARS_ERR_ARG;
+  if (!sizes_ok(B, N, V)) return MARS_ERR_ARG;
+  if (!(temperature >= 0.0f) || std::isinf(temperature)) return MARS_ERR_ARG;
+  if (logits_dtype != MARS_F32 && logits_dtype != MARS_BF16) return MARS_ERR_DTYPE;
+  HistSpec hs;
+  long ncounters = 4;
+  for (int h = 0; h < 3; ++h) {
+    const float lo = range[2 * h], hi = range[2 * h + 1];
+    if (!(lo < hi) || std::isinf(lo) || std::isinf(hi) || bins[h] < 1 || bins[h] > (1 << 20)) return MARS_ERR_ARG;
+    hs.lo[h] = lo; hs.hi[h] = hi; hs.bins[h] = bins[h];
+    hs.w[h] = static_cast<float>(static_cast<double>(bins[h]) / (static_cast<double>(hi) - static_cast<double>(lo)));
+    ncounters += bins[h] + 2;
+  }
+  if (ncounters > (1 << 20)) return MARS_ERR_ARG;
+  const Layout L = layout(B, N, V);
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0 || workspace_bytes < L.total)
+    return MARS_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const long rows = static_cast<long>(B) * N;
+  char* ws = static_cast<char*>(workspace);
+  Partial* partials = reinterpret_cast<Partial*>(ws + L.partials_off);
+  // The top-2 alone: the greedy form of the row reduction (no sum-exp); it also clears the counters.
+  ClearArgs clr = clear_args(ws, L, B, N, 1);
+  clr.counters = counts; clr.ncounters = ncounters;
+  if (launch_row_reduce(logits, logits_dtype, rows, V, L.splits, false, 0.0f, partials, clr, stream) != hipSuccess)
+    return MARS_ERR_HIP;
+  hipLaunchKernelGGL(margin_stats_kernel, dim3(static_cast<unsigned int>((rows + 15) / 16)), dim3(256), 0, stream,
+                     partials, static_cast<int>(rows), N, L.splits * kPartsPerItem, theta, indicator_scale(temperature),
+                     hs, rows_out, counts);
   return hipGetLastError() == hipSuccess ? MARS_OK : MARS_ERR_HIP;
 }
 

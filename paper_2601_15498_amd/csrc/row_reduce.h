@@ -79,11 +79,18 @@ __device__ __forceinline__ unsigned long long lane_value(unsigned long long v, i
   return (static_cast<unsigned long long>(hi) << 32) | lo;
 }
 
+// Memory the row reduction clears on behalf of the kernel that follows it on the stream.
+struct ClearArgs {
+  unsigned long long* xslots;  // exchange words of the sampling tail: [copies*B][N+2][xwords]
+  int N, B, xwords, copies;
+  unsigned int* counters;      // histogram counters (nullptr / 0 = none)
+  long ncounters;
+};
+
 template <typename T, int EPV, bool SAMPLING>
 __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __restrict__ logits, int V, int splits,
                                                                   int vecs_per_split, float c,
-                                                                  Partial* __restrict__ partials,
-                                                                  unsigned long long* __restrict__ xslots, int N, int xwords) {
+                                                                  Partial* __restrict__ partials, ClearArgs clr) {
   constexpr int U = kUnroll;
   constexpr int BV = kRowThreads * U;  // vectors per batch
   constexpr int NE = U * EPV;          // elements per lane per batch
@@ -101,16 +108,24 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   const int nfull = nv / BV;  // batches that need no bounds check
 
   // Exchange words of the tail kernel that follows on the stream (xwords per (request, exchange),
-  // N + 2 exchanges per request): cleared here so that the call needs no separate memset.
-  if (split == 0 && tid < xwords) {
+  // N + 2 exchanges per request, `copies` sets of B requests): cleared here so that the call
+  // needs no separate memset.  Likewise the counters a following kernel accumulates into.
+  if (split == 0 && tid < clr.xwords) {
+    const int N = clr.N;
     const int b = row / N, i = row - b * N;
-    unsigned long long* cells = xslots + static_cast<size_t>(b) * (N + 2) * xwords;
-    cells[static_cast<size_t>(i) * xwords + tid] = 0ull;
-    if (i == 0) {
-      cells[static_cast<size_t>(N) * xwords + tid] = 0ull;
-      cells[static_cast<size_t>(N + 1) * xwords + tid] = 0ull;
+    for (int k = 0; k < clr.copies; ++k) {
+      unsigned long long* cells =
+          clr.xslots + (static_cast<size_t>(k) * clr.B + b) * static_cast<size_t>(N + 2) * clr.xwords;
+      cells[static_cast<size_t>(i) * clr.xwords + tid] = 0ull;
+      if (i == 0) {
+        cells[static_cast<size_t>(N) * clr.xwords + tid] = 0ull;
+        cells[static_cast<size_t>(N + 1) * clr.xwords + tid] = 0ull;
+      }
     }
   }
+  for (long i = static_cast<long>(item) * kRowThreads + tid; i < clr.ncounters;
+       i += static_cast<long>(gridDim.x) * kRowThreads)
+    clr.counters[i] = 0u;
 
   float m1 = neg_inf(), m2 = neg_inf();  // best and second-best batch maximum of this lane
   int b1 = -1, b2 = -1;                  // the (distinct) batches they belong to
@@ -284,17 +299,62 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
 // Partial results per (row, split): one per wave of the work-group.
 constexpr int kPartsPerItem = kRowThreads / kWave;
 
-// One thread per row: merge its partial results into the statistics table.
+// Merge the partial results of every row into the statistics table (16 rows per work-group).
 __global__ __launch_bounds__(256) void merge_stats_kernel(const Partial* __restrict__ partials, int rows, int N,
                                                           int parts, const float* __restrict__ theta, float c,
-                                                          mars_row_stat* __restrict__ stats) {
-  // 16 rows per work-group of 256 threads
+                                                          Indicator ind, mars_row_stat* __restrict__ stats) {
   const int first = blockIdx.x * 16;
   const int n = min(16, rows - first);
   if (n <= 0) return;
-  merge_rows_coop<256>(partials + static_cast<size_t>(first) * parts, n, parts, c,
+  merge_rows_coop<256>(partials + static_cast<size_t>(first) * parts, n, parts, c, ind,
                        [&](int row) { return theta[(first + row) / N]; },
                        [&](int row, const mars_row_stat& st) { stats[first + row] = st; });
+}
+
+// Distributions of the top-2 statistics over the rows (appendix histogram figure of the paper:
+// top-1 logit, logit ratio z2/z1, probability ratio p2/p1, share of negative top-1 logits).
+// A histogram over [lo, hi) with `bins` equal cells owns bins + 2 counters: below lo, the cells,
+// at or above hi.  The cell is trunc(fl(fl(x - lo) * w)), w = fl32(bins / (hi - lo)), capped.
+struct HistSpec {
+  float lo[3], hi[3], w[3];
+  int bins[3];
+};
+__device__ __forceinline__ int hist_cell(float x, float lo, float hi, float w, int bins) {
+  if (x < lo) return 0;
+  if (!(x < hi)) return bins + 1;
+  const int k = static_cast<int>(__fmul_rn(__fsub_rn(x, lo), w));
+  return min(k, bins - 1) + 1;
+}
+// counters: [bins0+2 | bins1+2 | bins2+2 | rows, z1 < 0, z1 <= 0, low margin at theta], cleared by the
+// row reduction of the same call.  Rows with z1 <= 0 have no ratio (Sec. 3.3) and skip its histogram.
+__global__ __launch_bounds__(256) void margin_stats_kernel(const Partial* __restrict__ partials, int rows, int N,
+                                                           int parts, const float* __restrict__ theta, double cind,
+                                                           HistSpec hs, mars_margin_row* __restrict__ rows_out,
+                                                           unsigned int* __restrict__ counters) {
+  const int first = blockIdx.x * 16;
+  const int n = min(16, rows - first);
+  if (n <= 0) return;
+  unsigned int* h0 = counters;
+  unsigned int* h1 = h0 + hs.bins[0] + 2;
+  unsigned int* h2 = h1 + hs.bins[1] + 2;
+  unsigned int* summary = h2 + hs.bins[2] + 2;
+  const Indicator ind = {MARS_IND_LOGIT_RATIO, cind};
+  merge_rows_coop<256>(partials + static_cast<size_t>(first) * parts, n, parts, 0.0f, ind,
+                       [&](int row) { return theta[(first + row) / N]; },
+                       [&](int row, const mars_row_stat& st) {
+                         mars_margin_row m;
+                         m.z1 = st.z1; m.z2 = st.z2;
+                         m.ratio = st.z2 / st.z1;
+                         m.prob_ratio = prob_ratio(st.z1, st.z2, cind);
+                         if (rows_out) rows_out[first + row] = m;
+                         atomicAdd(&h0[hist_cell(m.z1, hs.lo[0], hs.hi[0], hs.w[0], hs.bins[0])], 1u);
+                         if (st.z1 > 0.0f) atomicAdd(&h1[hist_cell(m.ratio, hs.lo[1], hs.hi[1], hs.w[1], hs.bins[1])], 1u);
+                         atomicAdd(&h2[hist_cell(m.prob_ratio, hs.lo[2], hs.hi[2], hs.w[2], hs.bins[2])], 1u);
+                         atomicAdd(&summary[0], 1u);
+                         if (st.z1 < 0.0f) atomicAdd(&summary[1], 1u);
+                         if (!(st.z1 > 0.0f)) atomicAdd(&summary[2], 1u);
+                         if (st.relax_ok) atomicAdd(&summary[3], 1u);
+                       });
 }
 
 }  // namespace mars

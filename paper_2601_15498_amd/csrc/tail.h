@@ -35,6 +35,13 @@ struct TailArgs {
   int32_t* status;       // optional
   mars_req_diag* diag;   // optional
   int B, N, V, splits;   // splits = partial results per row
+  // Threshold sweep: B = K * Bd requests are verified, request b reading the inputs (logits,
+  // tokens, tree, draft distribution, uniforms, row partials) of request b % Bd with its own
+  // theta[b]; every output is indexed by b.  Bd == B without a sweep.
+  int Bd;
+  Indicator ind;         // which low-margin test (Sec. 3.3)
+  int32_t* out_tok;      // optional [B,N]: committed sequence V_out (Alg. 1), -1 padded
+  int32_t* out_len;      // optional [B]
   float c;               // log2(e) / T, 0 in greedy mode
   // sampling mode: G work-groups share one request and exchange partial sums
   int G;
@@ -49,8 +56,9 @@ template <int NT>
 __device__ int merge_and_validate(const TailArgs& a, int b, bool write_user_stats) {
   const int N = a.N;
   const size_t rb = static_cast<size_t>(b) * N;
+  const size_t rd = static_cast<size_t>(b % a.Bd) * N;  // where the request's inputs are
   const float theta = a.theta[b];
-  merge_rows_coop<NT>(a.partials + rb * a.splits, N, a.splits, a.c, [&](int) { return theta; },
+  merge_rows_coop<NT>(a.partials + rd * a.splits, N, a.splits, a.c, a.ind, [&](int) { return theta; },
                       [&](int row, const mars_row_stat& st) {
                         // Several work-groups of a request may write the workspace copy: identical bits.
                         a.stats_ws[rb + row] = st;
@@ -58,8 +66,8 @@ __device__ int merge_and_validate(const TailArgs& a, int b, bool write_user_stat
                       });
   int bad = 0;
   for (int i = threadIdx.x; i < N; i += NT) {
-    const int p = a.par[rb + i];
-    const int t = a.tok[rb + i];
+    const int p = a.par[rd + i];
+    const int t = a.tok[rd + i];
     if (i == 0) { if (p != -1) bad |= 1; }
     else {
       if (p < 0 || p >= i) bad |= 1;
@@ -80,10 +88,12 @@ __device__ void write_rejected_request(const TailArgs& a, int b, int status) {
     a.mask[r] = i == 0 ? 1 : 0;
     a.path[r] = -1;
     if (a.dec) a.dec[r] = 0;
+    if (a.out_tok && i > 0) a.out_tok[r] = -1;
   }
   if (threadIdx.x == 0) {
     a.len[b] = 0;
     a.bonus[b] = a.stats_ws[static_cast<size_t>(b) * N].id1;
+    if (a.out_tok) { a.out_tok[static_cast<size_t>(b) * N] = a.stats_ws[static_cast<size_t>(b) * N].id1; a.out_len[b] = 1; }
     if (a.status) a.status[b] = status;
     if (a.diag) { mars_req_diag d = {0.0f, 0.0f, 0, 0}; a.diag[b] = d; }
   }
@@ -101,6 +111,7 @@ __global__ __launch_bounds__(kGreedyThreads) void tail_greedy_kernel(TailArgs a)
   const int b = blockIdx.x;
   const int N = a.N;
   const size_t rb = static_cast<size_t>(b) * N;
+  const size_t rd = static_cast<size_t>(b % a.Bd) * N;
   const int status = merge_and_validate<NT>(a, b, true);
   if (status != MARS_REQ_OK) { write_rejected_request<NT>(a, b, status); return; }
 
@@ -108,8 +119,8 @@ __global__ __launch_bounds__(kGreedyThreads) void tail_greedy_kernel(TailArgs a)
   for (int i = threadIdx.x; i < N; i += NT) {
     int code = 0, anc = 0, dep = 0;
     if (i > 0) {
-      const int p = a.par[rb + i];
-      const int t = a.tok[rb + i];
+      const int p = a.par[rd + i];
+      const int t = a.tok[rd + i];
       const mars_row_stat st = a.stats_ws[rb + p];
       if (t == st.id1) code = MARS_DEC_EXACT;
       else if (t == st.id2 && st.relax_ok) code = MARS_DEC_RELAXED;
@@ -145,6 +156,7 @@ __global__ __launch_bounds__(kGreedyThreads) void tail_greedy_kernel(TailArgs a)
     a.mask[rb + i] = i == 0 ? 1 : 0;
     a.path[rb + i] = -1;
     if (a.dec) a.dec[rb + i] = 0;
+    if (a.out_tok) a.out_tok[rb + i] = -1;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -156,10 +168,13 @@ __global__ __launch_bounds__(kGreedyThreads) void tail_greedy_kernel(TailArgs a)
       a.mask[rb + n] = 1;
       a.path[rb + d - 1] = n;
       if (a.dec) a.dec[rb + n] = sh_code[n];
-      n = a.par[rb + n];
+      if (a.out_tok) a.out_tok[rb + d - 1] = a.tok[rd + n];  // V_out: the accepted drafts ...
+      n = a.par[rd + n];
     }
     a.len[b] = L;
-    a.bonus[b] = a.stats_ws[rb + e].id1;  // correction after a rejection, bonus after a leaf
+    const int correction = a.stats_ws[rb + e].id1;  // correction after a rejection, bonus after a leaf
+    a.bonus[b] = correction;
+    if (a.out_tok) { a.out_tok[rb + L] = correction; a.out_len[b] = L + 1; }  // ... then this token
     if (a.status) a.status[b] = MARS_REQ_OK;
     if (a.diag) { mars_req_diag dg = {0.0f, 0.0f, 0, e}; a.diag[b] = dg; }
   }
@@ -364,13 +379,15 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   const int b = blockIdx.x / G, g = blockIdx.x - b * G;
   const int N = a.N, V = a.V;
   const size_t rb = static_cast<size_t>(b) * N;
+  const int bd = b % a.Bd;  // the request whose inputs this (possibly swept) request reads
+  const size_t rd = static_cast<size_t>(bd) * N;
   const int tid = threadIdx.x;
   const int wave = tid / kWave, lane = tid % kWave;
   if (tid == 0) { sh_flag = 0; sh_bad = 0; }
   __syncthreads();
 
-  const T* __restrict__ zall = static_cast<const T*>(a.logits) + rb * static_cast<size_t>(V);
-  const TQ* __restrict__ qall = a.dprobs ? static_cast<const TQ*>(a.dprobs) + rb * static_cast<size_t>(V) : nullptr;
+  const T* __restrict__ zall = static_cast<const T*>(a.logits) + rd * static_cast<size_t>(V);
+  const TQ* __restrict__ qall = a.dprobs ? static_cast<const TQ*>(a.dprobs) + rd * static_cast<size_t>(V) : nullptr;
   const bool dense = qall != nullptr;
 
   // Prologue, one node per thread: validate tree and token, start the two gathers every
@@ -389,8 +406,8 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
       zx[t] = 0.0f; qx[t] = 1.0f;
       if (i < N) {
         const size_t r = rb + i;
-        const int p = a.par[r];
-        const int x = a.tok[r];
+        const int p = a.par[rd + i];
+        const int x = a.tok[rd + i];
         int bad = 0;
         if (i == 0) { if (p != -1) bad = 1; }
         else {
@@ -410,8 +427,8 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
         }
       }
     }
-    for (int i = tid; i <= N; i += NT) sh_u[i] = a.u[static_cast<size_t>(b) * (N + 1) + i];
-    merge_rows_coop<NT>(a.partials + rb * a.splits, N, a.splits, a.c, [&](int) { return theta; },
+    for (int i = tid; i <= N; i += NT) sh_u[i] = a.u[static_cast<size_t>(bd) * (N + 1) + i];
+    merge_rows_coop<NT>(a.partials + rd * a.splits, N, a.splits, a.c, a.ind, [&](int) { return theta; },
                         [&](int row, const mars_row_stat& st) {
                           sh_st[row] = st;
                           if (g == 0) {
@@ -552,6 +569,7 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
           a.mask[rb + k] = 1;
           a.path[rb + plen] = k;
           if (a.dec) a.dec[rb + k] = static_cast<uint8_t>(code);
+          if (a.out_tok) a.out_tok[rb + plen] = x;
         }
         accepted = k;
         break;
@@ -705,6 +723,13 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
     a.len[b] = plen;
     if (a.status) a.status[b] = sh_flag ? MARS_REQ_TIMEOUT : MARS_REQ_OK;
   }
+  // V_out (Alg. 1): the accepted drafts were written as they were accepted; the first work-group
+  // pads behind the slot of the final token, which the work-group that draws it fills in.  (No
+  // address is written by two work-groups.)
+  if (g == 0 && a.out_tok) {
+    for (int j = plen + 1 + tid; j < N; j += NT) a.out_tok[rb + j] = -1;
+    if (tid == 0) a.out_len[b] = plen + 1;
+  }
   if (g != owner) return;
 
   // The owning work-group locates the tile (every wave does, from the same LDS values).
@@ -815,6 +840,7 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   if (pick < 0) { pick = st.id1; pick_f = 0.0f; }  // degenerate: no mass anywhere
   if (lane == 0) {
     a.bonus[b] = pick;
+    if (a.out_tok) a.out_tok[rb + plen] = pick;
     if (a.diag) {
       mars_req_diag dg;
       dg.bonus_prob = total > 0.0 ? static_cast<float>(static_cast<double>(pick_f) / total) : 0.0f;
@@ -824,6 +850,56 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
       a.diag[b] = dg;
     }
   }
+}
+
+// ---------------------------------------------------------------- cache rows that stay
+// After the walk: the rows of the root and of the accepted nodes of every request, as flat row
+// numbers bd*N + node, request by request in path order ("standard rollback" of Sec. 3.4 keeps
+// exactly these), with the exclusive prefix sums of their counts.  One work-group per set of Bd
+// requests (per threshold of a sweep); unused entries of keep_rows are -1.
+constexpr int kKeepThreads = 256;
+__global__ __launch_bounds__(kKeepThreads) void compact_keep_kernel(const int32_t* __restrict__ out_len,
+                                                                    const int32_t* __restrict__ path, int Bd, int N,
+                                                                    int32_t* __restrict__ keep_rows,
+                                                                    int32_t* __restrict__ keep_offsets) {
+  constexpr int NT = kKeepThreads;
+  __shared__ int sh_wave[NT / kWave];
+  __shared__ int sh_carry;
+  const int k = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int32_t* len = out_len + static_cast<size_t>(k) * Bd;
+  const int32_t* pth = path + static_cast<size_t>(k) * Bd * N;
+  int32_t* rows = keep_rows + static_cast<size_t>(k) * Bd * N;
+  int32_t* offs = keep_offsets + static_cast<size_t>(k) * (Bd + 1);
+  if (tid == 0) sh_carry = 0;
+  __syncthreads();
+  for (int b0 = 0; b0 < Bd; b0 += NT) {
+    const int b = b0 + tid;
+    const int mine = b < Bd ? len[b] : 0;
+    // inclusive scan inside the wave, then across the waves of the work-group
+    int incl = mine;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      const int o = __shfl_up(incl, d, kWave);
+      if (lane >= d) incl += o;
+    }
+    if (lane == kWave - 1) sh_wave[wave] = incl;
+    __syncthreads();
+    int before = sh_carry;
+    for (int w = 0; w < wave; ++w) before += sh_wave[w];
+    const int start = before + incl - mine;
+    if (b < Bd) {
+      offs[b] = start;
+      rows[start] = b * N;  // the root's row
+      for (int j = 1; j < mine; ++j) rows[start + j] = b * N + pth[static_cast<size_t>(b) * N + j - 1];
+    }
+    __syncthreads();
+    if (tid == NT - 1) sh_carry = before + incl;
+    __syncthreads();
+  }
+  const int total = sh_carry;
+  if (tid == 0) offs[Bd] = total;
+  for (int i = total + tid; i < Bd * N; i += NT) rows[i] = -1;
 }
 
 }  // namespace mars

@@ -96,3 +96,93 @@ def compare(w, label=None, screened=True, cdf_guard=None):
                    sum_exp_rel=s_err, diag_rel=d_err)
     say(f"[ok]   {label}: {summary}")
     return summary
+
+
+INDICATOR_CODE = {"logit_ratio": M.MARS_IND_LOGIT_RATIO, "prob_ratio": M.MARS_IND_PROB_RATIO,
+                  "logit_gap": M.MARS_IND_LOGIT_GAP}
+
+
+def compare_ex(w, label=None, indicator="logit_ratio", thetas=None, cdf_guard=None, commit=True):
+    """mars_verify_ex against the oracle: chosen indicator, optional sweep thetas[K,B] (every output
+    with a leading K axis), committed sequence and kept cache rows.  Same bar as ``compare``."""
+    label = label or w.name
+    code = INDICATOR_CODE[indicator]
+    K = 1 if thetas is None else int(np.asarray(thetas).shape[0])
+    say(f"[case] {label}: B={w.B} N={w.N} V={w.V} dtype={w.dtype} T={w.temperature} "
+        f"dense_q={w.draft_probs is not None} indicator={indicator} K={K} commit={commit}")
+    ref = screen.screen_uniforms(w, cdf_guard=cdf_guard, indicator=code, thetas=thetas)
+    d = to_device(w)
+    th = d["theta"] if thetas is None else torch.from_numpy(np.ascontiguousarray(thetas, dtype=np.float32)).to(
+        d["logits"].device)
+    out = M.mars_verify_ex(d["logits"], d["draft_tokens"], d["tree_parent"], th, w.temperature, d["uniforms"],
+                           d["draft_probs"], indicator=code, n_theta=K, want_commit=commit)
+    torch.cuda.synchronize()
+    sampling = w.temperature > 0
+    for key in ("accept_len", "bonus_token", "request_status", "accept_mask", "path_idx", "decision"):
+        g = getattr(out, key).cpu().numpy()
+        assert g.shape == ref[key].shape, (key, g.shape, ref[key].shape)
+        bad = np.argwhere(g != ref[key])
+        assert bad.size == 0, (f"{label}: {key} differs at {bad[:6].tolist()}: gpu "
+                               f"{g[tuple(bad[0])]} ref {ref[key][tuple(bad[0])]}")
+    gs = out.stats.reshape(K, w.B * w.N, -1)
+    rs = ref["stats"].reshape(K, w.B * w.N)
+    for k in range(K):
+        assert_stats_match(gs[k], rs[k], sampling, f"{label}[k={k}]")
+    dg = {k: v.cpu().numpy().reshape(K, w.B) for k, v in M.unpack_diag(out.diag).items()}
+    rd = ref["diag"].reshape(K, w.B)
+    ok = ref["request_status"].reshape(K, w.B) == 0
+    assert np.array_equal(dg["last_node"][ok], rd["last_node"][ok]), f"{label}: last_node"
+    if sampling:
+        assert np.array_equal(dg["residual_passes"][ok], rd["residual_passes"][ok]), f"{label}: residual_passes"
+        a, b = dg["bonus_prob"][ok].astype(np.float64), rd["bonus_prob"][ok]
+        assert (np.abs(a - b) <= REL_TOL * np.abs(b)).all(), f"{label}: bonus_prob"
+    if commit:
+        for k in range(K):
+            sel = (lambda a: a[k]) if thetas is not None else (lambda a: a)
+            want = mars_ref.commit(w.draft_tokens, sel(ref["accept_len"]), sel(ref["path_idx"]), sel(ref["bonus_token"]))
+            for key in ("out_tokens", "out_len", "keep_rows", "keep_offsets"):
+                g = sel(getattr(out, key).cpu().numpy())
+                bad = np.argwhere(g != want[key])
+                assert bad.size == 0, f"{label}[k={k}]: {key} differs at {bad[:6].tolist()}"
+    summary = dict(mean_tau=np.round(ref["accept_len"].reshape(K, -1).mean(axis=1) + 1, 3).tolist(),
+                   relaxed=int((ref["decision"] == 2).sum()), low_margin_rows=int(ref["stats"]["relax_ok"].sum()))
+    say(f"[ok]   {label}: {summary}")
+    return summary
+
+
+def compare_margin(w, ranges, bins, label=None, edge_tol=1e-4):
+    """mars_margin_stats against the oracle.  Rows: z1, z2 and the fp32 ratio bit-exact, p2/p1 within
+    rel 1e-5.  Histograms of z1 and of the ratio, and the summary, bit-exact.  The histogram of p2/p1 goes
+    through an exponential evaluated differently on the two sides: rows whose p2/p1 lies within ``edge_tol``
+    cells of a cell boundary (the oracle reports the distance) may fall on either side of it, every other
+    row must be counted where the oracle counts it."""
+    label = label or w.name
+    say(f"[case] {label}: margin statistics B={w.B} N={w.N} V={w.V} dtype={w.dtype} T={w.temperature} bins={bins}")
+    ref = mars_ref.margin_stats(w.logits, w.theta, w.temperature, ranges, bins)
+    d = to_device(w)
+    rows, counts = M.mars_margin_stats(d["logits"], d["theta"], w.temperature, np.asarray(ranges).reshape(6), bins)
+    torch.cuda.synchronize()
+    rows = rows.cpu().numpy()
+    counts = counts.cpu().numpy().view(np.uint32)
+    r = ref["rows"].reshape(-1)
+    assert np.array_equal(rows[:, 0].astype(np.float64), r["z1"]) and np.array_equal(rows[:, 1].astype(np.float64), r["z2"])
+    with np.errstate(divide="ignore", invalid="ignore"):
+        want_ratio = r["z2"].astype(np.float32) / r["z1"].astype(np.float32)
+    assert np.array_equal(rows[:, 2], want_ratio, equal_nan=True), f"{label}: ratio"
+    pr = rows[:, 3].astype(np.float64)
+    rel = np.abs(pr - r["prob_ratio"]) / np.maximum(r["prob_ratio"], 1e-300)
+    rel[(pr == 0) & (r["prob_ratio"] < 1e-37)] = 0          # below the fp32 range: flushed to zero
+    assert rel.max() <= REL_TOL, f"{label}: p2/p1 rel err {rel.max():.3e}"
+    b0, b1, b2 = (int(b) + 2 for b in bins)
+    h0, h1, h2, summary = counts[:b0], counts[b0:b0 + b1], counts[b0 + b1:b0 + b1 + b2], counts[b0 + b1 + b2:]
+    assert h0.tolist() == ref["hist_z1"].tolist(), f"{label}: histogram of z1"
+    assert h1.tolist() == ref["hist_ratio"].tolist(), f"{label}: histogram of z2/z1"
+    assert summary.tolist() == ref["summary"].tolist(), f"{label}: summary {summary.tolist()} vs {ref['summary'].tolist()}"
+    diff = h2.astype(np.int64) - ref["hist_prob"].astype(np.int64)
+    near = int((ref["edge_dist"] < edge_tol).sum())
+    assert diff.sum() == 0 and np.abs(diff).sum() <= 2 * near, (
+        f"{label}: histogram of p2/p1 differs by {np.abs(diff).sum()} counts with {near} rows near a boundary")
+    assert h2.sum() == w.B * w.N
+    say(f"[ok]   {label}: p2/p1 rel {rel.max():.2e}, {near} boundary rows, moved {int(np.abs(diff).sum() // 2)}, "
+        f"summary {summary.tolist()}")
+    return dict(near=near, moved=int(np.abs(diff).sum() // 2), summary=summary.tolist())

@@ -27,8 +27,9 @@ def declared_functions():
 
 
 def test_header_declares_the_expected_entry_points():
-    assert declared_functions() == ["mars_row_reduce", "mars_row_stats", "mars_status_string", "mars_verify", "mars_version",
-                                    "mars_workspace_bytes"]
+    assert declared_functions() == ["mars_margin_stats", "mars_row_reduce", "mars_row_stats", "mars_status_string",
+                                    "mars_verify", "mars_verify_ex", "mars_version", "mars_workspace_bytes",
+                                    "mars_workspace_bytes_ex"]
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -43,6 +44,12 @@ def test_struct_sizes_match_the_binding():
     diag = re.search(r"typedef struct mars_req_diag \{(.*?)\}", text, re.S).group(1)
     assert len(re.findall(r"\b(float|int32_t)\b", re.sub(r"/\*.*?\*/", "", row, flags=re.S))) == binding.ROW_STAT_WORDS
     assert len(re.findall(r"\b(float|int32_t)\b", re.sub(r"/\*.*?\*/", "", diag, flags=re.S))) == binding.REQ_DIAG_WORDS
+    mrow = re.search(r"typedef struct mars_margin_row \{(.*?)\}", text, re.S).group(1)
+    assert len(re.findall(r"\bfloat\b", mrow)) == binding.MARGIN_ROW_WORDS
+    opt = re.sub(r"/\*.*?\*/", "", re.search(r"typedef struct mars_verify_options \{(.*?)\}", text, re.S).group(1), flags=re.S)
+    fields = re.findall(r"(int32_t\s*\*?)\s*(\w+);", opt)
+    assert [n for _, n in fields] == [n for n, _ in binding.VerifyOptionsStruct._fields_]
+    assert ["*" in t for t, _ in fields] == [t is ctypes.c_void_p for _, t in binding.VerifyOptionsStruct._fields_]
 
 
 def test_version_and_status_strings(lib):
@@ -86,6 +93,41 @@ def test_host_side_argument_errors_enqueue_nothing(lib):
     assert rr(p, 9, ctypes.c_float(0.0), 1, 1, 10, p, ctypes.c_size_t(1 << 20), null) == -2
     assert rr(p, 0, ctypes.c_float(-1.0), 1, 1, 10, p, ctypes.c_size_t(1 << 20), null) == -1
     assert rr(p, 0, ctypes.c_float(0.0), 1, 1, 10, null, ctypes.c_size_t(1 << 20), null) == -3
+    assert lib.mars_workspace_bytes_ex(2, 4, 100, 1) == lib.mars_workspace_bytes(2, 4, 100)
+    assert lib.mars_workspace_bytes_ex(2, 4, 100, 8) > lib.mars_workspace_bytes(2, 4, 100)
+    assert lib.mars_workspace_bytes_ex(2, 4, 100, 0) == 0 and lib.mars_workspace_bytes_ex(2, 4, 100, 65) == 0
+
+    from paper_2601_15498_amd.binding import VerifyOptionsStruct
+
+    def call_ex(opt, **kw):
+        a = dict(ok, **kw)
+        return lib.mars_verify_ex(a["logits"], a["ldt"], a["tok"], a["par"], a["dq"], a["ddt"], a["theta"],
+                                  ctypes.c_float(a["T"]), a["u"], a["B"], a["N"], a["V"], a["mask"], a["alen"],
+                                  a["path"], a["bonus"], a["dec"], a["st"], a["stats"], a["diag"], a["ws"],
+                                  ctypes.c_size_t(a["wsb"]), a["stream"], ctypes.byref(opt) if opt else None)
+
+    assert call_ex(None, logits=null) == -1                                   # NULL options = mars_verify
+    assert call_ex(VerifyOptionsStruct(3, 1, None, None, None, None)) == -1   # unknown indicator
+    assert call_ex(VerifyOptionsStruct(-1, 1, None, None, None, None)) == -1
+    assert call_ex(VerifyOptionsStruct(0, 65, None, None, None, None)) == -1  # too many thresholds
+    assert call_ex(VerifyOptionsStruct(0, -2, None, None, None, None)) == -1
+    assert call_ex(VerifyOptionsStruct(0, 1, 0x1000, None, None, None)) == -1  # commit outputs: all or none
+    assert call_ex(VerifyOptionsStruct(0, 1, 0x1000, 0x1000, 0x1000, None)) == -1
+    assert call_ex(VerifyOptionsStruct(1, 8, None, None, None, None), wsb=4096) == -3  # the sweep needs more workspace
+    ms = lib.mars_margin_stats
+    rg = (ctypes.c_float * 6)(0, 1, 0, 1, 0, 1)
+    bn = (ctypes.c_int32 * 3)(4, 4, 4)
+
+    def margin(logits=p, ldt=0, theta=p, T=0.0, B=1, N=1, V=10, rg=rg, bn=bn, counts=p, ws=p, wsb=1 << 20):
+        return ms(logits, ldt, theta, ctypes.c_float(T), B, N, V, rg, bn, null, counts, ws, ctypes.c_size_t(wsb), null)
+
+    assert margin(logits=null) == -1 and margin(theta=null) == -1 and margin(counts=null) == -1
+    assert margin(rg=None) == -1 and margin(bn=None) == -1
+    assert margin(ldt=4) == -2 and margin(T=-1.0) == -1 and margin(V=1) == -1
+    assert margin(rg=(ctypes.c_float * 6)(0, 1, 1, 1, 0, 1)) == -1           # lo >= hi
+    assert margin(bn=(ctypes.c_int32 * 3)(4, 0, 4)) == -1                    # no cells
+    assert margin(bn=(ctypes.c_int32 * 3)(1 << 20, 1 << 20, 4)) == -1        # too many counters
+    assert margin(ws=null) == -3 and margin(wsb=8) == -3
     rs = lib.mars_row_stats
     assert rs(null, 0, p, ctypes.c_float(0.0), 1, 1, 10, p, p, ctypes.c_size_t(1 << 20), null) == -1
     assert rs(p, 3, p, ctypes.c_float(0.0), 1, 1, 10, p, p, ctypes.c_size_t(1 << 20), null) == -2

@@ -1,0 +1,173 @@
+"""GPU parity of the entry points beyond the core pass -- mars_verify_ex (other low-margin indicators,
+threshold sweep, committed sequence with kept cache rows) and mars_margin_stats -- against the CPU
+oracle on the same seeded inputs.  Every test here needs a real MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from mars_inputs import f32_to_bf16_bits, make_config
+from tests.gpu_util import compare_ex, compare_margin, say
+from tests.test_gpu_parity import custom
+
+pytestmark = pytest.mark.gpu
+
+SWEEP = (0.84, 0.86, 0.88, 0.90, 0.92, 0.94, 0.96)   # the thresholds of the paper's ablation over theta
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu_and_lib():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2601_15498_amd import binding
+    binding.lib()
+
+
+def tiled(thetas, B):
+    return np.tile(np.asarray(thetas, np.float32)[:, None], (1, B))
+
+
+# ----------------------------------------------------------------------------- committed sequence + kept rows
+def test_commit_cfg0_greedy_chain():
+    compare_ex(make_config(0))
+
+
+@pytest.mark.parametrize("T", [0.0, 1.0])
+def test_commit_cfg1_tree(T):
+    compare_ex(make_config(1, temperature=T), label=f"commit_cfg1_T{T}")
+
+
+def test_commit_cfg2_full_dense_q():
+    compare_ex(make_config(2))
+
+
+def test_commit_cfg3_full():
+    compare_ex(make_config(3))
+
+
+def test_commit_cfg4_reduced_many_requests():
+    compare_ex(make_config(4, B=300, V=4096 + 24), label="commit_cfg4_B300_smallV")   # several scan rounds of 256
+
+
+def test_commit_of_rejected_requests():
+    rng = np.random.default_rng(3)
+    B, N, V = 5, 6, 64
+    z = rng.normal(0, 3, size=(B, N, V)).astype(np.float32)
+    par = np.tile(np.arange(-1, N - 1, dtype=np.int32), (B, 1))
+    tok = z.argmax(-1).astype(np.int32)
+    tok[:, 1:] = tok[:, :-1].copy()
+    par[1, 3] = 4          # parent after child: malformed tree
+    tok[3, 2] = V + 7      # token out of range
+    u = rng.random((B, N + 1)).astype(np.float32)
+    for T in (0.0, 1.0):
+        compare_ex(custom(f"commit_malformed_T{T}", z, tok, par, 0.9, T, u if T > 0 else None))
+
+
+# ----------------------------------------------------------------------------- other indicators (Sec. 3.3)
+@pytest.mark.parametrize("indicator,theta", [("prob_ratio", 0.3), ("logit_gap", 1.0)])
+def test_indicator_greedy_chain_f32(indicator, theta):
+    s = compare_ex(make_config(0, B=8, indicator=indicator, theta_choices=(theta,)), indicator=indicator,
+                   label=f"{indicator}_cfg0_B8")
+    assert s["relaxed"] > 0
+
+
+@pytest.mark.parametrize("indicator,theta", [("prob_ratio", 0.3), ("logit_gap", 1.0)])
+@pytest.mark.parametrize("T", [0.0, 1.0])
+def test_indicator_tree_bf16(indicator, theta, T):
+    compare_ex(make_config(1, temperature=T, B=4, indicator=indicator, theta_choices=(theta,)), indicator=indicator,
+               label=f"{indicator}_cfg1_B4_T{T}")
+
+
+def test_indicator_prob_ratio_dense_q_uses_temperature():
+    # T = 0.7: p2/p1 = exp(-gap / 0.7); per-request thresholds
+    s = compare_ex(make_config(2, B=3, indicator="prob_ratio", theta_choices=(0.02, 0.2)), indicator="prob_ratio",
+                   label="prob_ratio_cfg2_B3")
+    assert 0 < s["low_margin_rows"] < 180
+
+
+def test_indicator_gap_full_cfg3():
+    compare_ex(make_config(3, indicator="logit_gap", theta_choices=(0.5, 1.0, 2.0)), indicator="logit_gap",
+               label="logit_gap_cfg3")
+
+
+def test_indicator_negative_top_logits():
+    # every logit negative: the logit ratio never relaxes, the other two do
+    rng = np.random.default_rng(4)
+    B, N, V = 2, 8, 4096
+    z = (rng.normal(0, 1, size=(B, N, V)) - 30.0).astype(np.float32)
+    order = np.argsort(-z, axis=-1, kind="stable")
+    par = np.tile(np.arange(-1, N - 1, dtype=np.int32), (B, 1))
+    tok = np.zeros((B, N), np.int32)
+    tok[:, 1:] = order[:, :-1, 1]      # every draft is the runner-up
+    assert compare_ex(custom("neg_ratio", z, tok, par, 0.5, 0.0), indicator="logit_ratio")["relaxed"] == 0
+    assert compare_ex(custom("neg_gap", z, tok, par, 100.0, 0.0), indicator="logit_gap")["relaxed"] == B * (N - 1)
+    assert compare_ex(custom("neg_prob", z, tok, par, 1e-30, 0.0), indicator="prob_ratio")["relaxed"] == B * (N - 1)
+
+
+# ----------------------------------------------------------------------------- threshold sweep
+@pytest.mark.parametrize("T", [0.0, 1.0])
+def test_sweep_cfg1_seven_thresholds(T):
+    w = make_config(1, temperature=T, sweep_thetas=SWEEP)
+    s = compare_ex(w, thetas=tiled(SWEEP, w.B), label=f"sweep7_cfg1_T{T}")
+    if T == 0.0:
+        assert all(a >= b for a, b in zip(s["mean_tau"], s["mean_tau"][1:]))   # greedy: tau shrinks as theta rises
+
+
+def test_sweep_cfg2_full_headline_shape():
+    w = make_config(2, sweep_thetas=SWEEP)
+    compare_ex(w, thetas=tiled(SWEEP, w.B), label="sweep7_cfg2_full")
+
+
+def test_sweep_cfg3_per_request_thresholds():
+    w = make_config(3, B=16, sweep_thetas=(0.8, 0.99))
+    th = np.stack([w.theta, np.full(w.B, 0.8, np.float32), np.full(w.B, 0.99, np.float32)])
+    compare_ex(w, thetas=th, label="sweep3_cfg3_B16")
+
+
+def test_sweep_more_requests_than_compute_units():
+    w = make_config(4, B=40, V=8192 + 8, sweep_thetas=SWEEP + (1.5,))
+    compare_ex(w, thetas=tiled(SWEEP + (1.5,), w.B), label="sweep8_cfg4_B40")     # 320 walks, one work-group each
+
+
+def test_sweep_with_other_indicator():
+    ths = (0.1, 0.3, 0.6)
+    w = make_config(1, temperature=1.0, B=3, indicator="prob_ratio", theta_choices=(0.3,), sweep_thetas=ths)
+    compare_ex(w, thetas=tiled(ths, w.B), indicator="prob_ratio", label="sweep3_prob_ratio_cfg1_B3")
+
+
+# ----------------------------------------------------------------------------- margin statistics
+RANGES = ((-5.0, 35.0), (0.5, 1.0), (0.0, 1.0))
+BINS = (40, 50, 50)
+
+
+def test_margin_stats_cfg2_full():
+    s = compare_margin(make_config(2), RANGES, BINS)
+    assert s["summary"][0] == 960 and s["summary"][1] == 0      # no negative top-1 logit, as in the paper's figure
+
+
+def test_margin_stats_cfg0_f32_greedy():
+    compare_margin(make_config(0), RANGES, BINS)
+
+
+def test_margin_stats_cfg3_full_gumbel():
+    compare_margin(make_config(3), ((0.0, 40.0), (0.0, 1.0), (0.0, 1.0)), (64, 100, 1))
+
+
+def test_margin_stats_cfg4_reduced():
+    compare_margin(make_config(4, B=12), RANGES, (7, 13, 1000))
+
+
+def test_margin_stats_negative_and_zero_top_logits_ragged_vocab():
+    rng = np.random.default_rng(6)
+    B, N, V = 3, 11, 1000 + 3
+    z = rng.normal(0, 2, size=(B, N, V)).astype(np.float32)
+    z[0] -= 20.0                                   # negative top-1
+    z[1, :4] = np.minimum(z[1, :4], 0.0)           # top-1 exactly 0 (many ties)
+    z[2, 0, :] = -np.inf
+    z[2, 0, 5] = 3.0                               # a single unmasked token: z2 = -inf, ratio -inf, p2/p1 = 0
+    s = compare_margin(custom("margin_edge_rows", z, np.zeros((B, N), np.int32),
+                              np.tile(np.arange(-1, N - 1, dtype=np.int32), (B, 1)), 0.9, 0.5),
+                       ((-30.0, 10.0), (0.0, 1.0), (0.0, 1.0)), (8, 4, 4))
+    assert s["summary"][1] == N and s["summary"][2] == N + 4
+    zb = f32_to_bf16_bits(z)
+    compare_margin(custom("margin_edge_rows_bf16", zb, np.zeros((B, N), np.int32),
+                          np.tile(np.arange(-1, N - 1, dtype=np.int32), (B, 1)), 0.9, 0.0),
+                   ((-30.0, 10.0), (0.0, 1.0), (0.0, 1.0)), (8, 4, 4))
