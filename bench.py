@@ -1,17 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the MARS verification pass on one MI355X.
 
-One step = one call of ``mars_verify`` (the whole hot path: row reduction, margin test,
-acceptance, residual resampling, path and bonus-token selection) over one batch of synthetic
-input already resident in HBM.  The workload is the headline configuration: sampling
-verification at T = 0.7, B = 16 requests, a 60-node draft tree each, V = 151 936, bf16
-logits, dense fp32 draft distribution, theta = 0.9 (960 rows, 291.7 MB of logits per step).
-Four independently generated input sets are rotated so that a step never finds its
-logits in the 256 MB memory-side cache.
+One step = one call of the whole hot path (row reduction, margin test, acceptance, residual
+resampling, path and bonus-token selection) over one batch of synthetic input already resident in
+HBM.  The default workload is the headline configuration: sampling verification at T = 0.7,
+B = 16 requests, a 60-node draft tree each, V = 151 936, bf16 logits, dense fp32 draft
+distribution, theta = 0.9 (960 rows, 291.7 MB of logits per step).  Four independently generated
+input sets are rotated so that a step never finds its logits in the 256 MB memory-side cache.
 
-Prints ONE JSON line with the whole-job rows/s, the HBM roofline of the dominant kernel
-(the row reduction, timed by itself with HIP events on the stream it runs on) and the CPU
-oracle timed on the host cores of the same box.
+``--workload`` selects what a step is:
+  headline  mars_verify on the headline configuration (the default; the line the metric is quoted on)
+  commit    the same through mars_verify_ex with the committed sequence and the kept cache rows
+  sweep7    the same with seven thresholds per request (0.84 .. 0.96) from one read of the logits
+  margin    mars_margin_stats on the same logits (top-2 statistics per row and their histograms)
+  spd       mars_verify on chains of 6 drafts with a dense draft distribution, B = 128, T = 1
+
+Prints ONE JSON line with the whole-job rows/s, the HBM roofline of the dominant kernel (the row
+reduction, timed by itself with HIP events on the stream it runs on) and the CPU oracle timed on
+the host cores of the same box.
 """
 import argparse
 import hashlib
@@ -28,6 +34,21 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 N_BUFFERS = 4
 PARTIAL_BYTES = 24     # one partial result per (row, split, wave) written by the row reduction
 WAVES_PER_GROUP = 8    # waves per work-group of the row reduction
+SWEEP = (0.84, 0.86, 0.88, 0.90, 0.92, 0.94, 0.96)
+MARGIN_RANGES = (-5.0, 35.0, 0.5, 1.0, 0.0, 1.0)
+MARGIN_BINS = (40, 50, 50)
+
+WORKLOADS = {
+    "headline": dict(cfg=2, what="configs[2]: sampling T=0.7, B=16, 60-node tree per request, V=151936, "
+                                 "bf16 logits, dense fp32 draft distribution, theta=0.9"),
+    "commit": dict(cfg=2, what="configs[2] through mars_verify_ex, with the committed sequence and the kept cache rows"),
+    "sweep7": dict(cfg=2, what="configs[2] through mars_verify_ex with 7 thresholds per request (0.84..0.96), "
+                               "one read of the logits"),
+    "margin": dict(cfg=2, what="mars_margin_stats on the logits of configs[2]: top-2 statistics per row, histograms "
+                               "of z1, z2/z1, p2/p1 (40/50/50 cells)"),
+    "spd": dict(cfg=5, what="chains of 6 drafts (N=7), B=128, V=151936, bf16 logits, dense fp32 draft distribution, "
+                            "T=1, theta=0.9"),
+}
 
 
 def kernel_source_digest() -> str:
@@ -57,6 +78,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="headline")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for hardware-counter runs: a few launches of the row reduction on the headline "
@@ -78,12 +100,16 @@ def main() -> int:
         return 2
     M.lib()
     dev = torch.device("cuda:0")
-    spec = dict(CONFIGS[2])
+    wl = args.workload
+    spec = dict(CONFIGS[WORKLOADS[wl]["cfg"]])
     name = spec.pop("name")
     B, N, V = spec["B"], spec["N"], spec["V"]
     rows = B * N
     elt = 2 if spec["dtype"] == "bf16" else 4
     T = spec["temperature"]
+    K = len(SWEEP) if wl == "sweep7" else 1
+    if wl == "sweep7":
+        spec["sweep_thetas"] = SWEEP
 
     t_gen = time.perf_counter()
     sets, host0 = [], None
@@ -91,17 +117,21 @@ def main() -> int:
         w = make_workload(f"{name}_set{k}", seed=2 + 100 * k, **spec)
         if k == 0:
             host0 = w
+        theta = np.tile(np.asarray(SWEEP, np.float32)[:, None], (1, B)) if wl == "sweep7" else w.theta
         sets.append(dict(
             logits=torch.from_numpy(w.logits).to(dev),
             tok=torch.from_numpy(w.draft_tokens).to(dev),
             par=torch.from_numpy(w.tree_parent).to(dev),
-            theta=torch.from_numpy(w.theta).to(dev),
+            theta=torch.from_numpy(np.ascontiguousarray(theta)).to(dev),
             u=torch.from_numpy(w.uniforms).to(dev),
             q=torch.from_numpy(w.draft_probs).to(dev)))
     t_gen = time.perf_counter() - t_gen
 
-    ws = M.alloc_workspace(B, N, V, dev)
-    out = M.VerifyOutputs(B, N, dev)
+    ws = M.alloc_workspace(B, N, V, dev, n_theta=K)
+    out = M.VerifyOutputs(B, N, dev, n_theta=K, want_commit=(wl == "commit"))
+    margin_rows = torch.empty((rows, M.MARGIN_ROW_WORDS), dtype=torch.float32, device=dev)
+    margin_counts = torch.empty((M.margin_counts_len(MARGIN_BINS),), dtype=torch.int32, device=dev)
+    k1_temperature = 0.0 if wl == "margin" else T  # the statistics need the top-2 only: no sum-exp in that pass
 
     if args.pmc_probe:
         # Counter runs serialise kernels; keep the run short.  The copy moves exactly the bytes of one
@@ -109,14 +139,19 @@ def main() -> int:
         dst = torch.empty_like(sets[0]["logits"])
         for i in range(6):
             dst.copy_(sets[i % N_BUFFERS]["logits"])
-            M.mars_row_reduce(sets[i % N_BUFFERS]["logits"], T, ws)
+            M.mars_row_reduce(sets[i % N_BUFFERS]["logits"], k1_temperature, ws)
         torch.cuda.synchronize()
         print(json.dumps({"pmc_probe": True, "logits_bytes": rows * V * elt, "launches_each": 6}), flush=True)
         return 0
 
     def step(i):
         s = sets[i % N_BUFFERS]
-        M.mars_verify(s["logits"], s["tok"], s["par"], s["theta"], T, s["u"], s["q"], out, ws)
+        if wl in ("headline", "spd"):
+            M.mars_verify(s["logits"], s["tok"], s["par"], s["theta"], T, s["u"], s["q"], out, ws)
+        elif wl == "margin":
+            M.mars_margin_stats(s["logits"], s["theta"], T, MARGIN_RANGES, MARGIN_BINS, margin_rows, margin_counts, ws)
+        else:
+            M.mars_verify_ex(s["logits"], s["tok"], s["par"], s["theta"], T, s["u"], s["q"], out, ws, n_theta=K)
 
     for i in range(args.warmup):
         step(i)
@@ -128,7 +163,7 @@ def main() -> int:
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
     value = rows * args.steps / elapsed
-    tau = float(out.accept_len.float().mean().item()) + 1.0
+    tau = None if wl == "margin" else (out.accept_len.float().reshape(K, B).mean(dim=1) + 1.0).tolist()
 
     # Spread of one call: HIP events around each of up to 200 further calls (no host sync between them).
     n_ev = min(args.steps, 200)
@@ -143,12 +178,12 @@ def main() -> int:
 
     # The dominant kernel by itself: HIP events on the stream the kernel is launched on.
     for i in range(min(args.warmup, 10)):
-        M.mars_row_reduce(sets[i % N_BUFFERS]["logits"], T, ws)
+        M.mars_row_reduce(sets[i % N_BUFFERS]["logits"], k1_temperature, ws)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record()
     for i in range(args.steps):
-        M.mars_row_reduce(sets[i % N_BUFFERS]["logits"], T, ws)
+        M.mars_row_reduce(sets[i % N_BUFFERS]["logits"], k1_temperature, ws)
     e1.record()
     torch.cuda.synchronize()
     k1_ms = e0.elapsed_time(e1) / args.steps
@@ -156,8 +191,12 @@ def main() -> int:
     algo_bytes = rows * V * elt + rows * splits * WAVES_PER_GROUP * PARTIAL_BYTES
     achieved = algo_bytes / (k1_ms * 1e-3) / 1e9
 
+    metric = "verify rows/s + achieved HBM GB/s vs peak, B=16 tree-60 V=151936 bf16"
+    if wl != "headline":
+        metric = f"rows/s + achieved HBM GB/s vs peak, workload '{wl}'"
+    k1_name = "row_reduce_kernel<bf16, 8 per load, %s>" % ("top-2 only" if wl == "margin" else "sampling")
     result = {
-        "metric": "verify rows/s + achieved HBM GB/s vs peak, B=16 tree-60 V=151936 bf16",
+        "metric": metric,
         "value": value,
         "unit": "rows/s",
         "n_gpus": 1,
@@ -169,16 +208,16 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "configs[2]: sampling T=0.7, B=16, 60-node tree per request, V=151936, "
-                               "bf16 logits, dense fp32 draft distribution, theta=0.9",
+        "config": {"workload": WORKLOADS[wl]["what"],
                    "B": B, "N": N, "V": V, "rows_per_step": rows, "logits_dtype": spec["dtype"],
-                   "temperature": T, "input_sets_rotated": N_BUFFERS, "mean_tau": tau,
+                   "temperature": T, "thresholds_per_request": K, "input_sets_rotated": N_BUFFERS, "mean_tau": tau,
                    "whole_pass_logits_GBps": rows * V * elt / (ms_per_step * 1e-3) / 1e9,
                    "call_us_p10": pct[10], "call_us_median": pct[50], "call_us_p90": pct[90],
                    "input_generation_s": round(t_gen, 1)},
-        "roofline": {"bound": "hbm", "kernel": "row_reduce_kernel<bf16, 8 per load, sampling>",
+        "roofline": {"bound": "hbm", "kernel": k1_name,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(),
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic() if wl in ("headline", "commit", "sweep7") else None,
                      "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_us": k1_ms * 1e3},
     }
 
@@ -186,21 +225,33 @@ def main() -> int:
         from oracle import mars_ref
         cores = os.cpu_count() or 1
         cores = min(cores, 16) if "OMP_NUM_THREADS" not in os.environ else int(os.environ["OMP_NUM_THREADS"])
+
+        def oracle_pass():
+            h = host0
+            if wl == "margin":
+                mars_ref.margin_stats(h.logits, h.theta, T, MARGIN_RANGES, MARGIN_BINS)
+            elif wl == "sweep7":
+                mars_ref.verify_sweep(h.logits, h.draft_tokens, h.tree_parent,
+                                      np.tile(np.asarray(SWEEP, np.float32)[:, None], (1, B)), T, h.uniforms,
+                                      h.draft_probs)
+            else:
+                o = mars_ref.verify(h.logits, h.draft_tokens, h.tree_parent, h.theta, T, h.uniforms, h.draft_probs)
+                if wl == "commit":
+                    mars_ref.commit(h.draft_tokens, o["accept_len"], o["path_idx"], o["bonus_token"])
+
         mars_ref.set_threads(cores)
         reps, cpu_s = 0, 0.0
         while reps < 3 or (cpu_s * cores < 10.0 and reps < 20):
             t = time.perf_counter()
-            mars_ref.verify(host0.logits, host0.draft_tokens, host0.tree_parent, host0.theta, T,
-                            host0.uniforms, host0.draft_probs)
+            oracle_pass()
             cpu_s += time.perf_counter() - t
             reps += 1
         mars_ref.set_threads(1)
         t = time.perf_counter()
-        mars_ref.verify(host0.logits, host0.draft_tokens, host0.tree_parent, host0.theta, T,
-                        host0.uniforms, host0.draft_probs)
+        oracle_pass()
         one_s = time.perf_counter() - t
         result["cpu_baseline"] = {"value": rows * reps / cpu_s, "unit": "rows/s", "cores": cores, "kind": "oracle",
-                                  "sample": f"the whole configs[2] workload (960 rows, input set 0), {reps} passes, "
+                                  "sample": f"the whole workload ({rows} rows, input set 0), {reps} passes, "
                                             f"{cpu_s:.1f} s wall",
                                   "single_thread_value": rows / one_s}
     print(json.dumps(result), flush=True)

@@ -292,6 +292,12 @@ CONFIGS = {
             temperature=1.0, tree={"kind": "tree", "depth": 5, "max_children": 4},
             background="normal3", plant_frac=0.6, r_range=(0.85, 1.00), theta_choices=(0.9,),
             dense_q=False),
+    # Not one of the five stated configurations: the paper's "framework-decoupled" experiment runs the rule
+    # inside standard speculative decoding with gamma = 6 drafts per step and a real draft distribution
+    # (T = 1); the same shape at a serving batch size.
+    5: dict(name="spd_B128_chain6_V151936_bf16_T1_dense_q", B=128, N=7, V=151936, dtype="bf16",
+            temperature=1.0, tree={"kind": "chain"}, background="normal3", plant_frac=0.5,
+            r_range=(0.80, 1.00), theta_choices=(0.9,), dense_q=True),
 }
 
 

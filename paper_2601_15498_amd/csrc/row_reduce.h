@@ -338,6 +338,11 @@ __global__ __launch_bounds__(256) void margin_stats_kernel(const Partial* __rest
   unsigned int* h1 = h0 + hs.bins[0] + 2;
   unsigned int* h2 = h1 + hs.bins[1] + 2;
   unsigned int* summary = h2 + hs.bins[2] + 2;
+  // The summary counters would take one atomic per row on a single address each: they are
+  // gathered in LDS first and leave the work-group as one atomic per counter.
+  __shared__ unsigned int sh_sum[4];
+  if (threadIdx.x < 4) sh_sum[threadIdx.x] = 0u;
+  __syncthreads();
   const Indicator ind = {MARS_IND_LOGIT_RATIO, cind};
   merge_rows_coop<256>(partials + static_cast<size_t>(first) * parts, n, parts, 0.0f, ind,
                        [&](int row) { return theta[(first + row) / N]; },
@@ -350,11 +355,14 @@ __global__ __launch_bounds__(256) void margin_stats_kernel(const Partial* __rest
                          atomicAdd(&h0[hist_cell(m.z1, hs.lo[0], hs.hi[0], hs.w[0], hs.bins[0])], 1u);
                          if (st.z1 > 0.0f) atomicAdd(&h1[hist_cell(m.ratio, hs.lo[1], hs.hi[1], hs.w[1], hs.bins[1])], 1u);
                          atomicAdd(&h2[hist_cell(m.prob_ratio, hs.lo[2], hs.hi[2], hs.w[2], hs.bins[2])], 1u);
-                         atomicAdd(&summary[0], 1u);
-                         if (st.z1 < 0.0f) atomicAdd(&summary[1], 1u);
-                         if (!(st.z1 > 0.0f)) atomicAdd(&summary[2], 1u);
-                         if (st.relax_ok) atomicAdd(&summary[3], 1u);
+                         if (st.z1 < 0.0f) atomicAdd(&sh_sum[1], 1u);
+                         if (!(st.z1 > 0.0f)) atomicAdd(&sh_sum[2], 1u);
+                         if (st.relax_ok) atomicAdd(&sh_sum[3], 1u);
                        });
+  __syncthreads();
+  if (threadIdx.x == 0) sh_sum[0] = static_cast<unsigned int>(n);
+  __syncthreads();
+  if (threadIdx.x < 4 && sh_sum[threadIdx.x] != 0u) atomicAdd(&summary[threadIdx.x], sh_sum[threadIdx.x]);
 }
 
 }  // namespace mars

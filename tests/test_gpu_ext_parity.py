@@ -171,3 +171,13 @@ def test_margin_stats_negative_and_zero_top_logits_ragged_vocab():
     compare_margin(custom("margin_edge_rows_bf16", zb, np.zeros((B, N), np.int32),
                           np.tile(np.arange(-1, N - 1, dtype=np.int32), (B, 1)), 0.9, 0.0),
                    ((-30.0, 10.0), (0.0, 1.0), (0.0, 1.0)), (8, 4, 4))
+
+
+# ----------------------------------------------------------------------------- SPD-shaped workload
+def test_spd_chains_dense_q_reduced():
+    compare_ex(make_config(5, B=6), label="spd_B6")
+
+
+def test_spd_chains_dense_q_full():
+    s = compare_ex(make_config(5), label="spd_B128")
+    assert s["low_margin_rows"] > 0
