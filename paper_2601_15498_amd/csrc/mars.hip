@@ -285,7 +285,7 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
   // The waits are bounded: should foreign work keep part of the grid from being scheduled, the
   // affected requests end with MARS_REQ_TIMEOUT instead of hanging.  (A cooperative launch
   // would have the runtime check residency, at the price of ~20 us per call on this stack.)
-  if (hipLaunchKernel(kernel, dim3(static_cast<unsigned int>(K * B) * a.G), dim3(kSamplingThreads), params, 0,
+  if (hipLaunchKernel(kernel, dim3(static_cast<unsigned int>(K * B) * a.G), dim3(resident ? kSamplingThreads : kStreamingThreads), params, 0,
                       stream) !=
       hipSuccess)
     return MARS_ERR_HIP;

@@ -14,7 +14,8 @@
 namespace mars {
 
 constexpr int kGreedyThreads = 256;
-constexpr int kSamplingThreads = 512;
+constexpr int kSamplingThreads = 512;    // sampling tail whose slices stay in registers
+constexpr int kStreamingThreads = 1024;  // sampling tail that streams its slices: more loads in flight per compute unit
 constexpr int kMaxTiles = 512;  // CDF tiles kept in LDS for the final draw
 
 struct TailArgs {
@@ -306,13 +307,19 @@ template <typename T, typename TQ>
 struct RowView {
   const T* zrow;
   const TQ* qrow;   // nullptr = one-hot draft distribution
+  bool use_q;       // false: this pass does not look at q (no rejection at this node so far), skip its loads
   int V;
   bool vec_ok;
   float z1, c, inv_S;
   Chain ch;
   __device__ __forceinline__ void load(int gi, float (&z)[8], float (&q)[8]) const {
     load8<T>(zrow, gi, V, vec_ok, neg_inf(), z);
-    if (qrow) load8<TQ>(qrow, gi, V, vec_ok, 0.0f, q);
+    if (qrow && use_q) {
+      load8<TQ>(qrow, gi, V, vec_ok, 0.0f, q);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) q[e] = 0.0f;
+    }
   }
   __device__ __forceinline__ float f(const float (&z)[8], const float (&q)[8], int gi, int e) const {
     return eval_f(z[e], qrow ? q[e] : 0.0f, gi * 8 + e, z1, c, inv_S, qrow != nullptr, ch);
@@ -351,14 +358,86 @@ __device__ double residual_mass_slice(const RowView<T, TQ>& rv, int g_begin, int
   return part;
 }
 
+// Prefix sums over the n <= kMaxTiles tile sums in LDS, by one wave: lane l owns the contiguous
+// run of `per` tiles starting at l*per; the runs are summed in index order and scanned across the
+// lanes.  Every lane ends with the same answers, and the total and the search use the same
+// additions (any wave of the work-group may call these and obtains the same bits).
+struct TilePrefix {
+  double mine;  // sum of the lane's run
+  double incl;  // sum of the runs of lanes 0..l
+};
+__device__ __forceinline__ TilePrefix tile_prefix(const double* sh_tile, int n, int per, int lane) {
+  TilePrefix p;
+  p.mine = 0.0;
+  for (int i = 0; i < per; ++i) {
+    const int t = lane * per + i;
+    if (t < n) p.mine += sh_tile[t];
+  }
+  p.incl = p.mine;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const double o = __shfl_up(p.incl, d, kWave);
+    if (lane >= d) p.incl += o;
+  }
+  return p;
+}
+__device__ __forceinline__ double tile_total(const double* sh_tile, int n, int lane) {
+  const int per = (n + kWave - 1) / kWave;
+  return __shfl(tile_prefix(sh_tile, n, per, lane).incl, kWave - 1, kWave);
+}
+// The first tile whose inclusive prefix (on top of `before`) exceeds target, and the prefix in
+// front of it; when rounding leaves none, the last tile with mass (tile 0 if there is none).
+__device__ __forceinline__ void tile_find(const double* sh_tile, int n, int lane, double before, double target,
+                                          int& tile, double& cum) {
+  const int per = (n + kWave - 1) / kWave;
+  const TilePrefix p = tile_prefix(sh_tile, n, per, lane);
+  const double excl = before + (p.incl - p.mine);
+  int my_last = -1;
+  for (int i = 0; i < per; ++i) {
+    const int t = lane * per + i;
+    if (t < n && sh_tile[t] > 0.0) my_last = t;
+  }
+  const unsigned long long has = __ballot(my_last >= 0);
+  const int last_tile = has != 0ull ? __shfl(my_last, 63 - __clzll(static_cast<long long>(has)), kWave) : 0;
+  const unsigned long long hit = __ballot(before + p.incl > target);
+  int found = -1;
+  double front = 0.0;
+  if (hit != 0ull) {
+    const int hl = __ffsll(static_cast<long long>(hit)) - 1;
+    if (lane == hl) {
+      double run = excl;
+      for (int i = 0; i < per && found < 0; ++i) {
+        const int t = lane * per + i;
+        if (t < n) {
+          if (run + sh_tile[t] > target) { found = t; front = run; } else run += sh_tile[t];
+        }
+      }
+    }
+    found = __shfl(found, hl, kWave);
+    front = __shfl(front, hl, kWave);
+  }
+  if (found < 0) {  // rounding: the last tile with mass, with the prefix in front of it
+    found = last_tile;
+    const int ol = found / per;
+    double run = excl;
+    for (int i = 0; i < per; ++i) {
+      const int t = lane * per + i;
+      if (t < found) run += sh_tile[t];
+    }
+    front = __shfl(run, ol, kWave);
+  }
+  tile = found;
+  cum = front;
+}
+
 constexpr int kMaxGroupsPerRequest = 32;   // work-groups that may share one request
 constexpr float kClosedFormMinNorm = 0.1f; // one-hot residual: Z = 1 - f(x) is used when at least this
 constexpr int kResident = 4;               // groups of eight elements a thread can keep in registers
 
 // RESIDENT: every slice is at most kResident groups per thread (decided by the host from G and V).
 template <typename T, typename TQ, bool RESIDENT>
-__global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArgs a) {
-  constexpr int NT = kSamplingThreads;
+__global__ __launch_bounds__(RESIDENT ? kSamplingThreads : kStreamingThreads) void tail_sampling_kernel(TailArgs a) {
+  constexpr int NT = RESIDENT ? kSamplingThreads : kStreamingThreads;
   constexpr int NW = NT / kWave;
   __shared__ int16_t sh_par[MARS_MAX_NODES];     // parent of every node
   __shared__ int32_t sh_tok[MARS_MAX_NODES];     // draft token of every node
@@ -526,6 +605,7 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
     rv.zrow = zall + static_cast<size_t>(cnode) * V;
     rv.qrow = dense ? qall + static_cast<size_t>(cnode) * V : nullptr;
     rv.z1 = st.z1; rv.inv_S = 1.0f / st.sum_exp;
+    rv.use_q = dense;  // a rejection pass subtracts q
     rv.ch.n = 0;
     pending_norm = false;
     have = false;
@@ -625,6 +705,9 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
 
   // ---------------------------------------------------------------- inverse-CDF draw from f at cnode
   const mars_row_stat st = sh_st[cnode];
+  // Without a rejection at this node f is the plain softmax: the draft distribution is not read.
+  // (A resident slice that was loaded for a rejection already holds it.)
+  rv.use_q = dense && rv.ch.n > 0;
   // Tiles of the slice, in vocabulary order.  Resident slice: a tile is one step (64 groups).
   // Otherwise wave w owns a contiguous run of steps and a tile is `rep` consecutive steps of it.
   const int steps_per_wave = (nsteps + NW - 1) / NW;
@@ -683,9 +766,8 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
       }
     }
     __syncthreads();
-    // slice total = sum of its tiles in index order (the same additions the search below repeats)
-    double wg_total = 0.0;
-    for (int t = 0; t < ntiles; ++t) wg_total += sh_tile[t];
+    // slice total = sum of its tiles, taken by the same prefix scheme the search below uses
+    const double wg_total = tile_total(sh_tile, ntiles, lane);
     total = exchange_sum<NT>(a, b, g, N + attempt, wg_total, sh_part, &sh_flag);
     // Which work-group's slice holds the target?  The last one with mass if rounding leaves none.
     const double target = static_cast<double>(u[N]) * total;
@@ -735,20 +817,7 @@ __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_kernel(TailArg
   // The owning work-group locates the tile (every wave does, from the same LDS values).
   int tile = -1;
   double cum = before;
-  if (total > 0.0) {
-    int last_tile = -1;
-    for (int t = 0; t < ntiles; ++t) {
-      if (sh_tile[t] > 0.0) last_tile = t;
-      if (tile < 0) {
-        if (cum + sh_tile[t] > target) tile = t; else cum += sh_tile[t];
-      }
-    }
-    if (tile < 0) {  // rounding: fall back to the last tile with mass
-      tile = last_tile < 0 ? 0 : last_tile;
-      cum = before;
-      for (int t = 0; t < tile; ++t) cum += sh_tile[t];
-    }
-  }
+  if (total > 0.0) tile_find(sh_tile, ntiles, lane, before, target, tile, cum);
   // One wave finishes: the one holding the tile in registers, or wave 0 re-reading it.
   const int finder = (resident && tile >= 0) ? tile % NW : 0;
   if (wave != finder) return;
