@@ -216,6 +216,11 @@ int mars_verify(const void* logits, int logits_dtype,
  *                 reduction runs once, and the per-request part runs for every (k, b) on the same
  *                 inputs; EVERY output of mars_verify gains a leading axis of length K
  *                 (accept_mask [K,B,N], accept_len [K,B], ..., stats [K,B*N], diag [K,B]).
+ *   spin_limit    sampling mode: polls a work-group waits for a partner's partial sum before it
+ *                 flags the request MARS_REQ_TIMEOUT and carries on (every wait in the library is
+ *                 bounded).  0 = the default, on the order of a second.  Only of interest to
+ *                 callers that share the GPU with other work, and to tests of that path.
+ *   reserved      must be 0.
  *   out_tokens    device out, optional, [K,B,N] int32: the committed sequence V_out of Alg. 1 -- the
  *                 tokens of the accepted nodes in path order, then the correction / bonus token,
  *                 then -1.
@@ -229,6 +234,8 @@ int mars_verify(const void* logits, int logits_dtype,
 typedef struct mars_verify_options {
   int32_t  indicator;
   int32_t  n_theta;
+  int32_t  spin_limit;
+  int32_t  reserved;
   int32_t* out_tokens;
   int32_t* out_len;
   int32_t* keep_rows;
@@ -246,8 +253,8 @@ size_t mars_workspace_bytes_ex(int B, int N, int V, int n_theta);
  * shapes stated above when n_theta > 1 and workspace >= mars_workspace_bytes_ex(B,N,V,n_theta);
  * options == NULL is mars_verify.  n_theta * B requests are verified side by side, which in
  * sampling mode leaves fewer work-groups per request.  Errors as for mars_verify, plus
- * MARS_ERR_ARG for an unknown indicator, n_theta outside [0, MARS_MAX_THETAS], or some but not all
- * of the four commit outputs.
+ * MARS_ERR_ARG for an unknown indicator, n_theta outside [0, MARS_MAX_THETAS], a negative
+ * spin_limit, a non-zero reserved field, or some but not all of the four commit outputs.
  */
 int mars_verify_ex(const void* logits, int logits_dtype,
                    const int32_t* draft_tokens, const int32_t* tree_parent,

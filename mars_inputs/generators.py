@@ -310,6 +310,7 @@ def make_config(cfg: int, *, temperature: Optional[float] = None, threads: Optio
     if temperature is not None:
         spec["temperature"] = temperature
     name = spec.pop("name")
+    seed = spec.pop("seed", cfg)
     if override or temperature is not None:
         name += "_variant"
-    return make_workload(name, seed=cfg, threads=threads, **spec)
+    return make_workload(name, seed=seed, threads=threads, **spec)

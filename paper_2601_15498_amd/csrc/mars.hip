@@ -207,11 +207,13 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
   using namespace mars;
   if (!logits || !draft_tokens || !tree_parent || !theta || !accept_mask || !accept_len || !path_idx || !bonus_token)
     return MARS_ERR_ARG;
-  int K = 1, indicator = MARS_IND_LOGIT_RATIO;
+  int K = 1, indicator = MARS_IND_LOGIT_RATIO, spin_limit = 0;
   int32_t *out_tokens = nullptr, *out_len = nullptr, *keep_rows = nullptr, *keep_offsets = nullptr;
   if (options) {
     K = options->n_theta == 0 ? 1 : options->n_theta;
     indicator = options->indicator;
+    spin_limit = options->spin_limit;
+    if (spin_limit < 0 || options->reserved != 0) return MARS_ERR_ARG;
     out_tokens = options->out_tokens; out_len = options->out_len;
     keep_rows = options->keep_rows; keep_offsets = options->keep_offsets;
   }
@@ -235,7 +237,11 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
   Partial* partials = reinterpret_cast<Partial*>(ws + L.partials_off);
   const float c = log2e_over_t(temperature);
 
-  const ClearArgs clr = clear_args(ws, L, B, N, K);
+  ClearArgs clr = clear_args(ws, L, B, N, K);
+  if (sampling && request_status) {  // the sampling tail only raises a request's status
+    clr.counters = reinterpret_cast<unsigned int*>(request_status);
+    clr.ncounters = static_cast<long>(K) * B;
+  }
   if (launch_row_reduce(logits, logits_dtype, rows, V, L.splits, sampling, c, partials, clr, stream) != hipSuccess)
     return MARS_ERR_HIP;
 
@@ -246,7 +252,8 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
   a.stats = stats;
   a.stats_ws = reinterpret_cast<mars_row_stat*>(ws + L.stats_off);
   a.G = sampling ? L.G : 1;
-  a.spin_limit = 1 << 20;  // on the order of a second of polling before a request gives up on its partners
+  // by default on the order of a second of polling before a request gives up on its partners
+  a.spin_limit = spin_limit > 0 ? spin_limit : 1 << 20;
   a.xslots = clr.xslots;
   a.mask = accept_mask; a.len = accept_len; a.path = path_idx; a.bonus = bonus_token;
   a.dec = decision; a.status = request_status; a.diag = diag;

@@ -801,10 +801,11 @@ __global__ __launch_bounds__(RESIDENT ? kSamplingThreads : kStreamingThreads) vo
   }
   if (pending_norm) last_norm = static_cast<float>(total);
   const double target = static_cast<double>(u[N]) * total;
-  if (g == 0 && tid == 0) {
-    a.len[b] = plen;
-    if (a.status) a.status[b] = sh_flag ? MARS_REQ_TIMEOUT : MARS_REQ_OK;
-  }
+  if (g == 0 && tid == 0) a.len[b] = plen;
+  // The request's status was cleared to MARS_REQ_OK by the row reduction of this call.  Any
+  // work-group that gave up on a partner marks the request: its own view of the sums, and with
+  // it whatever it wrote, may be off even if the other work-groups saw every value.
+  if (tid == 0 && a.status && sh_flag) atomicMax(&a.status[b], static_cast<int32_t>(MARS_REQ_TIMEOUT));
   // V_out (Alg. 1): the accepted drafts were written as they were accepted; the first work-group
   // pads behind the slot of the final token, which the work-group that draws it fills in.  (No
   // address is written by two work-groups.)

@@ -107,13 +107,15 @@ def test_host_side_argument_errors_enqueue_nothing(lib):
                                   ctypes.c_size_t(a["wsb"]), a["stream"], ctypes.byref(opt) if opt else None)
 
     assert call_ex(None, logits=null) == -1                                   # NULL options = mars_verify
-    assert call_ex(VerifyOptionsStruct(3, 1, None, None, None, None)) == -1   # unknown indicator
-    assert call_ex(VerifyOptionsStruct(-1, 1, None, None, None, None)) == -1
-    assert call_ex(VerifyOptionsStruct(0, 65, None, None, None, None)) == -1  # too many thresholds
-    assert call_ex(VerifyOptionsStruct(0, -2, None, None, None, None)) == -1
-    assert call_ex(VerifyOptionsStruct(0, 1, 0x1000, None, None, None)) == -1  # commit outputs: all or none
-    assert call_ex(VerifyOptionsStruct(0, 1, 0x1000, 0x1000, 0x1000, None)) == -1
-    assert call_ex(VerifyOptionsStruct(1, 8, None, None, None, None), wsb=4096) == -3  # the sweep needs more workspace
+    assert call_ex(VerifyOptionsStruct(3, 1, 0, 0, None, None, None, None)) == -1   # unknown indicator
+    assert call_ex(VerifyOptionsStruct(-1, 1, 0, 0, None, None, None, None)) == -1
+    assert call_ex(VerifyOptionsStruct(0, 65, 0, 0, None, None, None, None)) == -1  # too many thresholds
+    assert call_ex(VerifyOptionsStruct(0, -2, 0, 0, None, None, None, None)) == -1
+    assert call_ex(VerifyOptionsStruct(0, 1, 0, 0, 0x1000, None, None, None)) == -1  # commit outputs: all or none
+    assert call_ex(VerifyOptionsStruct(0, 1, 0, 0, 0x1000, 0x1000, 0x1000, None)) == -1
+    assert call_ex(VerifyOptionsStruct(1, 8, 0, 0, None, None, None, None), wsb=4096) == -3  # the sweep needs more workspace
+    assert call_ex(VerifyOptionsStruct(0, 1, -5, 0, None, None, None, None)) == -1  # negative spin limit
+    assert call_ex(VerifyOptionsStruct(0, 1, 0, 7, None, None, None, None)) == -1   # reserved field set
     ms = lib.mars_margin_stats
     rg = (ctypes.c_float * 6)(0, 1, 0, 1, 0, 1)
     bn = (ctypes.c_int32 * 3)(4, 4, 4)

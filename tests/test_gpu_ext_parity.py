@@ -181,3 +181,87 @@ def test_spd_chains_dense_q_reduced():
 def test_spd_chains_dense_q_full():
     s = compare_ex(make_config(5), label="spd_B128")
     assert s["low_margin_rows"] > 0
+
+
+# ----------------------------------------------------------------------------- failure handling, graphs
+def test_bounded_wait_flags_the_request_and_every_kernel_exits():
+    # Forced from the host: with a spin limit of one poll a work-group gives up on partners that are a
+    # moment late.  Every wait being bounded, the call completes; a request is either flagged
+    # MARS_REQ_TIMEOUT (outputs undefined but in range) or every exchange of every one of its work-groups
+    # succeeded, and then its outputs are exact.  The next call with the default limit is exact again.
+    from oracle import screen
+    from paper_2601_15498_amd import binding as M
+    from tests.gpu_util import to_device
+    w = make_config(2, B=3)                     # 32 work-groups per request, several exchanges each
+    ref = screen.screen_uniforms(w)
+    d = to_device(w)
+    ws = M.alloc_workspace(w.B, w.N, w.V, d["logits"].device)
+    out = M.mars_verify_ex(d["logits"], d["draft_tokens"], d["tree_parent"], d["theta"], w.temperature,
+                           d["uniforms"], d["draft_probs"], workspace=ws, spin_limit=1)
+    torch.cuda.synchronize()
+    st = out.request_status.cpu().numpy()
+    say(f"[info] spin_limit=1: request_status {st.tolist()}")
+    assert set(st.tolist()) <= {0, 3}
+    alen = out.accept_len.cpu().numpy()
+    assert ((alen >= 0) & (alen < w.N)).all()
+    for b in np.nonzero(st == 0)[0]:
+        for key in ("accept_len", "bonus_token", "accept_mask", "path_idx", "decision"):
+            assert np.array_equal(getattr(out, key).cpu().numpy()[b], ref[key][b]), (b, key)
+    out = M.mars_verify_ex(d["logits"], d["draft_tokens"], d["tree_parent"], d["theta"], w.temperature,
+                           d["uniforms"], d["draft_probs"], workspace=ws)
+    torch.cuda.synchronize()
+    assert (out.request_status.cpu().numpy() == 0).all()
+    for key in ("accept_len", "bonus_token", "accept_mask", "path_idx", "decision"):
+        assert np.array_equal(getattr(out, key).cpu().numpy(), ref[key]), key
+
+
+@pytest.mark.parametrize("T", [0.0, 0.7])
+def test_graph_replays_equal_eager(T):
+    # The calls only enqueue kernels (no allocation, no memset, no synchronisation), so a caller may
+    # capture them in a HIP graph.  Every replay, with eager work and synchronisations in between and the
+    # inputs changed under the graph, must equal the eager result on the same inputs.
+    from paper_2601_15498_amd import binding as M
+    from tests.gpu_util import to_device
+    ws_list = [make_config(2, B=4, temperature=T), make_config(2, B=4, temperature=T, seed=77)]
+    devs = [to_device(w) for w in ws_list]
+    B, N, V = ws_list[0].B, ws_list[0].N, ws_list[0].V
+    dev = devs[0]["logits"].device
+    cur = {k: (None if v is None else v.clone()) for k, v in devs[0].items()}   # static inputs of the graph
+    if T == 0.0:
+        cur["uniforms"] = None
+        cur["draft_probs"] = None
+    ws = M.alloc_workspace(B, N, V, dev)
+    out_g = M.VerifyOutputs(B, N, dev, want_commit=True)
+    out_e = M.VerifyOutputs(B, N, dev, want_commit=True)
+
+    def call(out):
+        M.mars_verify_ex(cur["logits"], cur["draft_tokens"], cur["tree_parent"], cur["theta"], T, cur["uniforms"],
+                         cur["draft_probs"], out=out, workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call(out_g)                      # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call(out_g)
+    keys = ("accept_len", "bonus_token", "accept_mask", "path_idx", "decision", "request_status", "out_tokens",
+            "out_len", "keep_rows", "keep_offsets", "stats")
+    for rep in range(4):
+        src = devs[rep % 2]
+        for k, v in cur.items():
+            if v is not None:
+                v.copy_(src[k])
+        torch.cuda.synchronize()
+        call(out_e)
+        torch.cuda.synchronize()
+        want = {k: getattr(out_e, k).clone() for k in keys}
+        for k in keys:
+            getattr(out_g, k).fill_(-7 if getattr(out_g, k).dtype != torch.uint8 else 9)
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in keys:
+            assert torch.equal(getattr(out_g, k), want[k]), (rep, k)
+    say(f"[ok]   graph T={T}: 4 replays equal eager")
