@@ -21,9 +21,6 @@ static size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // Splits per row: a function of (rows, V) only, so that the workspace size does not depend on
 // the element type.
 static int choose_splits(long rows, int V) {
-#ifdef MARS_FORCE_SPLITS  // build-time tuning hook
-  return MARS_FORCE_SPLITS;
-#endif
   long want = (kTargetItems + rows - 1) / rows;
   long cap = V / kMinSplitElems;
   if (cap < 1) cap = 1;
