@@ -187,7 +187,8 @@ def main() -> int:
     e1.record()
     torch.cuda.synchronize()
     k1_ms = e0.elapsed_time(e1) / args.steps
-    splits = max(1, min((1024 + rows - 1) // rows, V // 8192))  # the library's rule: 2 for 960 rows
+    target = min(1024, max(128, (rows * V) >> 16))               # the library's rule for the work-groups it aims for
+    splits = max(1, min((target + rows - 1) // rows, V // 8192))  # 2 splits per row for 960 rows
     algo_bytes = rows * V * elt + rows * splits * WAVES_PER_GROUP * PARTIAL_BYTES
     achieved = algo_bytes / (k1_ms * 1e-3) / 1e9
 

@@ -262,11 +262,22 @@ __device__ __forceinline__ void merge_rows_coop(const Partial* __restrict__ part
     double S = 0.0;
     if (live) {
       const Partial* __restrict__ p = partials + static_cast<size_t>(row) * parts;
-      for (int s = sub; s < parts; s += 16) {
-        const Partial q = p[s];
-        if (q.id1 >= 0) top2_insert(k1, k2, make_key(q.z1, q.id1));
-        if (q.id2 >= 0) top2_insert(k1, k2, make_key(q.z2, q.id2));
-        if (c > 0.0f && q.s > 0.0f) absorb_sum(R, S, q.ref, static_cast<double>(q.s));
+      // Four loads are issued before the first is used: a row with many partial results costs a
+      // quarter of the memory round trips.
+      constexpr int kBatch = 4;
+      for (int s0 = sub; s0 < parts; s0 += 16 * kBatch) {
+        Partial q[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+          const int s = s0 + 16 * j;
+          if (s < parts) q[j] = p[s]; else { q[j].id1 = -1; q[j].id2 = -1; q[j].s = 0.0f; q[j].z1 = 0.0f; q[j].z2 = 0.0f; q[j].ref = 0.0f; }
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+          if (q[j].id1 >= 0) top2_insert(k1, k2, make_key(q[j].z1, q[j].id1));
+          if (q[j].id2 >= 0) top2_insert(k1, k2, make_key(q[j].z2, q[j].id2));
+          if (c > 0.0f && q[j].s > 0.0f) absorb_sum(R, S, q[j].ref, static_cast<double>(q[j].s));
+        }
       }
     }
     // Butterfly over the sixteen lanes: at every step the two sides hold disjoint sets of

@@ -12,16 +12,24 @@
 
 namespace mars {
 
-constexpr int kTargetItems = 1024;      // aim for at least this many work-groups in the row reduction
-constexpr int kMinSplitElems = 8192;    // but keep every split at least this long
+constexpr int kMaxTargetItems = 1024;   // work-groups the row reduction aims for on a large input (4 per compute unit)
+constexpr int kMinTargetItems = 128;    // ... and on a small one
+constexpr int kItemElemsLog2 = 16;      // in between: about one work-group per 65 536 elements
+constexpr int kMinSplitElems = 8192;    // no split shorter than this
 constexpr size_t kAlign = 256;
 
 static size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // Splits per row: a function of (rows, V) only, so that the workspace size does not depend on
-// the element type.
+// the element type.  A large input needs several work-groups per compute unit to keep the memory
+// pipeline full.  A small one (a single request) is bound by latency, not by bandwidth: the row
+// reduction takes about as long with a few hundred work-groups as with a thousand, while every
+// split adds partial results that the per-request kernel behind it has to merge.
 static int choose_splits(long rows, int V) {
-  long want = (kTargetItems + rows - 1) / rows;
+  long target = (rows * static_cast<long>(V)) >> kItemElemsLog2;
+  if (target < kMinTargetItems) target = kMinTargetItems;
+  if (target > kMaxTargetItems) target = kMaxTargetItems;
+  long want = (target + rows - 1) / rows;
   long cap = V / kMinSplitElems;
   if (cap < 1) cap = 1;
   if (want > cap) want = cap;

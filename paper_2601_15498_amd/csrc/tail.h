@@ -13,7 +13,7 @@
 
 namespace mars {
 
-constexpr int kGreedyThreads = 256;
+constexpr int kGreedyThreads = 1024;  // 64 rows merged at a time
 constexpr int kSamplingThreads = 512;    // sampling tail whose slices stay in registers
 constexpr int kStreamingThreads = 1024;  // sampling tail that streams its slices: more loads in flight per compute unit
 constexpr int kMaxTiles = 512;  // CDF tiles kept in LDS for the final draw
