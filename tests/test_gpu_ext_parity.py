@@ -265,3 +265,56 @@ def test_graph_replays_equal_eager(T):
         for k in keys:
             assert torch.equal(getattr(out_g, k), want[k]), (rep, k)
     say(f"[ok]   graph T={T}: 4 replays equal eager")
+
+
+# ----------------------------------------------------------------------------- edge sizes of the extended entry point
+def test_ex_root_only_and_tiny_vocab_with_maximum_thresholds():
+    # N = 1: nothing to verify, the committed sequence is the one token drawn from the root row; V = 2;
+    # 64 thresholds per request (the maximum), both modes, every indicator.
+    z = np.array([[[1.5, 1.25]], [[-2.0, 3.0]], [[0.5, 0.5]]], np.float32)
+    tok = np.zeros((3, 1), np.int32)
+    par = -np.ones((3, 1), np.int32)
+    u = np.array([[0.3, 0.9], [0.2, 0.05], [0.7, 0.4999]], np.float32)
+    ths = np.linspace(0.05, 1.3, 64).astype(np.float32)
+    for T in (0.0, 0.9):
+        for ind in ("logit_ratio", "prob_ratio", "logit_gap"):
+            compare_ex(custom(f"root_only_T{T}_{ind}", z, tok, par, 0.9, T, u if T > 0 else None),
+                       indicator=ind, thetas=tiled(ths, 3), label=f"root_only_K64_T{T}_{ind}")
+
+
+@pytest.mark.parametrize("T", [0.0, 1.0])
+def test_ex_maximum_nodes_with_commit_and_sweep(T):
+    # N = 1024 (the maximum), a deep chain mixed with a bushy part, two thresholds
+    rng = np.random.default_rng(21)
+    B, N, V = 2, 1024, 512
+    z = (rng.normal(0, 1, size=(B, N, V)) + 6.0).astype(np.float32)
+    par = np.zeros((B, N), np.int32)
+    par[:, 0] = -1
+    for b in range(B):
+        for i in range(1, N):
+            par[b, i] = i - 1 if i < 700 else rng.integers(0, i)
+    order = np.argsort(-z, axis=-1, kind="stable")
+    tok = np.zeros((B, N), np.int32)
+    for b in range(B):
+        for i in range(1, N):
+            tok[b, i] = order[b, par[b, i], 0 if rng.random() < 0.9 else 1]
+    u = rng.random((B, N + 1)).astype(np.float32)
+    w = custom(f"max_nodes_ex_T{T}", z, tok, par, 0.9, T, u if T > 0 else None)
+    s = compare_ex(w, thetas=np.array([[0.5, 0.5], [2.0, 0.93]], np.float32), label=f"max_nodes_ex_T{T}")
+    if T == 0.0:
+        assert max(s["mean_tau"]) > 5      # long accepted chains: the path outputs are exercised in depth
+
+
+def test_ex_tiny_vocab_every_indicator_sampling_dense():
+    rng = np.random.default_rng(22)
+    B, N = 6, 7
+    for V in (2, 3, 9):
+        z = rng.normal(0, 2, size=(B, N, V)).astype(np.float32)
+        q = rng.dirichlet(np.ones(V), size=(B, N)).astype(np.float64)
+        q = (q / q.sum(-1, keepdims=True)).astype(np.float32)
+        par = np.tile(np.array([-1, 0, 0, 1, 1, 2, 3], np.int32), (B, 1))
+        tok = rng.integers(0, V, size=(B, N)).astype(np.int32)
+        u = rng.random((B, N + 1)).astype(np.float32)
+        for ind, th in (("prob_ratio", 0.4), ("logit_gap", 0.8)):
+            compare_ex(custom(f"tiny_V{V}_{ind}", z, tok, par, th, 0.8, u, q), indicator=ind, cdf_guard=5e-6,
+                       label=f"tiny_V{V}_{ind}")
