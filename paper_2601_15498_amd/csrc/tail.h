@@ -246,10 +246,11 @@ __device__ __forceinline__ float eval_f(float z, float q, int v, float z1, float
   return f;
 }
 
+// Sum over the work-group.  The caller keeps a barrier between two calls (the exchange that follows
+// every call has one), so the staging array needs none in front of the write.
 template <int NT>
 __device__ __forceinline__ double block_sum(double v, double* sh) {
   v = wave_sum(v);
-  __syncthreads();
   if (threadIdx.x % kWave == 0) sh[threadIdx.x / kWave] = v;
   __syncthreads();
   double t = 0.0;
@@ -280,20 +281,19 @@ __device__ double exchange_sum(const TailArgs& a, int b, int g, int idx, double 
     __hip_atomic_store(&cell[2 * g], pack_tagged(hi), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(&cell[2 * g + 1], pack_tagged(lo), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  if (threadIdx.x < G) {
-    double v = 0.0;
-    for (int h = 0; h < 2; ++h) {
-      unsigned long long w = 0;
-      int spins = 0;
-      for (;;) {
-        w = __hip_atomic_load(&cell[2 * threadIdx.x + h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((w >> 32) != 0ull) break;
-        if (++spins > a.spin_limit) { *sh_flag = 1; break; }
-        __builtin_amdgcn_s_sleep(1);
-      }
-      v += static_cast<double>(__uint_as_float(static_cast<unsigned int>(w)));
+  if (threadIdx.x < 2 * G) {
+    // One wave polls all 2*G words at once: lane 2i the head of work-group i's value, lane 2i+1 its tail.
+    unsigned long long w = 0;
+    int spins = 0;
+    for (;;) {
+      w = __hip_atomic_load(&cell[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if ((w >> 32) != 0ull) break;
+      if (++spins > a.spin_limit) { *sh_flag = 1; break; }
+      __builtin_amdgcn_s_sleep(1);
     }
-    sh_part[threadIdx.x] = v;
+    double v = static_cast<double>(__uint_as_float(static_cast<unsigned int>(w)));
+    v += __shfl_down(v, 1, kWave);  // even lanes: head + tail
+    if ((threadIdx.x & 1) == 0) sh_part[threadIdx.x >> 1] = v;
   }
   __syncthreads();
   double t = 0.0;
