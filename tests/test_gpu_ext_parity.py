@@ -318,3 +318,52 @@ def test_ex_tiny_vocab_every_indicator_sampling_dense():
         for ind, th in (("prob_ratio", 0.4), ("logit_gap", 0.8)):
             compare_ex(custom(f"tiny_V{V}_{ind}", z, tok, par, th, 0.8, u, q), indicator=ind, cdf_guard=5e-6,
                        label=f"tiny_V{V}_{ind}")
+
+
+# ----------------------------------------------------------------------------- seeded sweep over shapes and options
+def sweep_case(rng, seed, case):
+    """One randomly shaped, valid workload with its options."""
+    from mars_inputs import make_workload
+    B = int(rng.choice([1, 2, 3, 5, 9, 17, 40]))
+    N = int(rng.choice([1, 2, 3, 8, 17, 33, 64]))
+    V = int(rng.choice([2, 7, 8, 63, 64, 520, 1024, 4095, 4096, 8200, 16392, 40003]))
+    dtype = str(rng.choice(["f32", "bf16"]))
+    T = float(rng.choice([0.0, 0.0, 0.6, 1.0, 1.7]))
+    dense = bool(rng.random() < 0.5) and T > 0
+    ind, th = [("logit_ratio", 0.9), ("prob_ratio", 0.35), ("logit_gap", 1.25)][int(rng.integers(3))]
+    K = int(rng.choice([1, 1, 2, 5]))
+    ths = tuple(float(x) for x in np.round(np.linspace(0.6 * th, 1.3 * th, K), 4)) if K > 1 else ()
+    tree = {"kind": "chain"}
+    if rng.random() >= 0.4 and N >= 4:
+        depth, fan = int(rng.integers(2, 7)), int(rng.integers(2, 5))
+        depth = min(depth, N - 1)
+        while sum(fan ** d for d in range(depth + 1)) < N:   # the tree must be able to hold N nodes
+            depth += 1
+        tree = {"kind": "tree", "depth": depth, "max_children": fan}
+    w = make_workload(f"sweep_s{seed}_c{case}", B=B, N=N, V=V, dtype=dtype, temperature=T, tree=tree,
+                      background=str(rng.choice(["normal3", "gumbel2"])), plant_frac=0.5 if V >= 64 else 0.0,
+                      theta_choices=(th,), dense_q=dense, seed=5000 + 10 * seed + case, indicator=ind,
+                      sweep_thetas=ths, threads=1)
+    return w, ind, ths, tree
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_seeded_sweep_over_shapes_and_options(seed):
+    # Valid inputs of many shapes: vocabulary sizes around the vector and tile boundaries, chains and trees,
+    # both storage types, greedy and sampling with one-hot and dense q, every indicator, one to five thresholds.
+    # A case whose uniforms cannot be kept clear of the decision thresholds (a tiny vocabulary whose residual
+    # mass is below the conditioning floor whatever is drawn) has no well-posed expected value and is left out.
+    rng = np.random.default_rng(1000 + seed)
+    ran = 0
+    for case in range(6):
+        w, ind, ths, tree = sweep_case(rng, seed, case)
+        try:
+            compare_ex(w, indicator=ind, thetas=tiled(ths, w.B) if ths else None,
+                       cdf_guard=5e-6 if w.V > 20000 else None,
+                       label=f"sweep_s{seed}_c{case}: ind={ind} K={max(1, len(ths))} tree={tree}")
+            ran += 1
+        except RuntimeError as e:
+            if "guard band not reached" not in str(e):
+                raise
+            say(f"[skip] sweep_s{seed}_c{case}: {e}")
+    assert ran >= 4
