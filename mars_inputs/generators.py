@@ -230,6 +230,8 @@ def make_workload(name: str, *, B: int, N: int, V: int, dtype: str, temperature:
     the guard band around theta is kept on that quantity.  ``sweep_thetas`` are further thresholds (of a
     sweep over theta) every row also keeps clear of."""
     assert dtype in ("f32", "bf16")
+    if tree["kind"] != "chain" and tree["max_children"] > V:
+        raise ValueError("siblings carry distinct draft tokens: max_children cannot exceed V")
     sampling = temperature > 0
     rth = _rng(seed, 6000, 0)
     theta = np.asarray(theta_choices, dtype=np.float32)[rth.integers(len(theta_choices), size=B)]

@@ -335,7 +335,7 @@ def sweep_case(rng, seed, case):
     ths = tuple(float(x) for x in np.round(np.linspace(0.6 * th, 1.3 * th, K), 4)) if K > 1 else ()
     tree = {"kind": "chain"}
     if rng.random() >= 0.4 and N >= 4:
-        depth, fan = int(rng.integers(2, 7)), int(rng.integers(2, 5))
+        depth, fan = int(rng.integers(2, 7)), min(int(rng.integers(2, 5)), V)   # siblings carry distinct tokens
         depth = min(depth, N - 1)
         while sum(fan ** d for d in range(depth + 1)) < N:   # the tree must be able to hold N nodes
             depth += 1
