@@ -367,3 +367,22 @@ def test_seeded_sweep_over_shapes_and_options(seed):
                 raise
             say(f"[skip] sweep_s{seed}_c{case}: {e}")
     assert ran >= 4
+
+
+def test_margin_stats_many_cells_and_no_row_output():
+    # half a million cells for the top-1 logit (the counters are cleared by the row reduction itself), and the
+    # per-row table left out (rows_out = NULL)
+    from oracle import mars_ref
+    from paper_2601_15498_amd import binding as M
+    from tests.gpu_util import to_device
+    w = make_config(3, B=16)
+    ranges, bins = ((0.0, 64.0), (0.0, 1.0), (0.0, 1.0)), (1 << 19, 3, 2)
+    compare_margin(w, ranges, bins, label="margin_many_cells")
+    d = to_device(w)
+    rows, counts = M.mars_margin_stats(d["logits"], d["theta"], w.temperature, np.asarray(ranges).reshape(6), bins,
+                                       want_rows=False)
+    torch.cuda.synchronize()
+    assert rows is None
+    ref = mars_ref.margin_stats(w.logits, w.theta, w.temperature, ranges, bins)
+    c = counts.cpu().numpy().view(np.uint32)
+    assert np.array_equal(c[:bins[0] + 2], ref["hist_z1"]) and c[-4:].tolist() == ref["summary"].tolist()
