@@ -15,6 +15,13 @@ input sets are rotated so that a step never finds its logits in the 256 MB memor
   margin    mars_margin_stats on the same logits (top-2 statistics per row and their histograms)
   spd       mars_verify on chains of 6 drafts with a dense draft distribution, B = 128, T = 1
 
+The timed steps are issued round-robin on ``--streams`` HIP streams (default 2), each with its own
+workspace and outputs: the library keeps no state and calls with different workspaces may overlap,
+so the latency-bound per-request kernel of one step runs beside the bandwidth-bound row reduction
+of the next, as a server verifying two micro-batches would have it.  ``value`` is the throughput of
+that; the line also carries the one-stream throughput and the latency of single calls
+(``config.single_stream_*``, ``config.call_us_*``).
+
 Prints ONE JSON line with the whole-job rows/s, the HBM roofline of the dominant kernel (the row
 reduction, timed by itself with HIP events on the stream it runs on) and the CPU oracle timed on
 the host cores of the same box.
@@ -79,6 +86,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="headline")
+    ap.add_argument("--streams", type=int, default=2, help="HIP streams the timed steps alternate over")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for hardware-counter runs: a few launches of the row reduction on the headline "
@@ -127,10 +135,14 @@ def main() -> int:
             q=torch.from_numpy(w.draft_probs).to(dev)))
     t_gen = time.perf_counter() - t_gen
 
-    ws = M.alloc_workspace(B, N, V, dev, n_theta=K)
-    out = M.VerifyOutputs(B, N, dev, n_theta=K, want_commit=(wl == "commit"))
-    margin_rows = torch.empty((rows, M.MARGIN_ROW_WORDS), dtype=torch.float32, device=dev)
-    margin_counts = torch.empty((M.margin_counts_len(MARGIN_BINS),), dtype=torch.int32, device=dev)
+    n_streams = max(1, args.streams)
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    wss = [M.alloc_workspace(B, N, V, dev, n_theta=K) for _ in range(n_streams)]
+    outs = [M.VerifyOutputs(B, N, dev, n_theta=K, want_commit=(wl == "commit")) for _ in range(n_streams)]
+    margin_rows = [torch.empty((rows, M.MARGIN_ROW_WORDS), dtype=torch.float32, device=dev) for _ in range(n_streams)]
+    margin_counts = [torch.empty((M.margin_counts_len(MARGIN_BINS),), dtype=torch.int32, device=dev)
+                     for _ in range(n_streams)]
+    ws, out = wss[0], outs[0]
     k1_temperature = 0.0 if wl == "margin" else T  # the statistics need the top-2 only: no sum-exp in that pass
 
     if args.pmc_probe:
@@ -144,26 +156,39 @@ def main() -> int:
         print(json.dumps({"pmc_probe": True, "logits_bytes": rows * V * elt, "launches_each": 6}), flush=True)
         return 0
 
-    def step(i):
+    def step(i, j=0):
+        """One pass over input set i with the workspace and outputs of slot j, on the current stream."""
         s = sets[i % N_BUFFERS]
         if wl in ("headline", "spd"):
-            M.mars_verify(s["logits"], s["tok"], s["par"], s["theta"], T, s["u"], s["q"], out, ws)
+            M.mars_verify(s["logits"], s["tok"], s["par"], s["theta"], T, s["u"], s["q"], outs[j], wss[j])
         elif wl == "margin":
-            M.mars_margin_stats(s["logits"], s["theta"], T, MARGIN_RANGES, MARGIN_BINS, margin_rows, margin_counts, ws)
+            M.mars_margin_stats(s["logits"], s["theta"], T, MARGIN_RANGES, MARGIN_BINS, margin_rows[j],
+                                margin_counts[j], wss[j])
         else:
-            M.mars_verify_ex(s["logits"], s["tok"], s["par"], s["theta"], T, s["u"], s["q"], out, ws, n_theta=K)
+            M.mars_verify_ex(s["logits"], s["tok"], s["par"], s["theta"], T, s["u"], s["q"], outs[j], wss[j], n_theta=K)
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    def timed(n_steps, n_str):
+        """Wall time of n_steps passes issued round-robin over n_str streams (0: the current stream)."""
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n_steps):
+            if n_str == 0:
+                step(i)
+            else:
+                with torch.cuda.stream(streams[i % n_str]):
+                    step(i, i % n_str)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    timed(args.warmup, n_streams)
+    elapsed = timed(args.steps, n_streams)
     ms_per_step = elapsed / args.steps * 1e3
     value = rows * args.steps / elapsed
     tau = None if wl == "margin" else (out.accept_len.float().reshape(K, B).mean(dim=1) + 1.0).tolist()
+    statuses = 0 if wl == "margin" else int(sum((o.request_status != 0).sum().item() for o in outs))
+    # the same passes one after the other on one stream
+    timed(min(args.warmup, 10), 0)
+    single_elapsed = timed(args.steps, 0)
 
     # Spread of one call: HIP events around each of up to 200 further calls (no host sync between them).
     n_ev = min(args.steps, 200)
@@ -212,6 +237,9 @@ def main() -> int:
         "config": {"workload": WORKLOADS[wl]["what"],
                    "B": B, "N": N, "V": V, "rows_per_step": rows, "logits_dtype": spec["dtype"],
                    "temperature": T, "thresholds_per_request": K, "input_sets_rotated": N_BUFFERS, "mean_tau": tau,
+                   "streams": n_streams, "requests_with_nonzero_status": statuses,
+                   "single_stream_ms_per_step": single_elapsed / args.steps * 1e3,
+                   "single_stream_rows_per_s": rows * args.steps / single_elapsed,
                    "whole_pass_logits_GBps": rows * V * elt / (ms_per_step * 1e-3) / 1e9,
                    "call_us_p10": pct[10], "call_us_median": pct[50], "call_us_p90": pct[90],
                    "input_generation_s": round(t_gen, 1)},

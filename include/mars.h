@@ -194,7 +194,10 @@ int mars_row_stats(const void* logits, int logits_dtype, const float* theta,
  * order with uniforms[b,N].
  *
  * Returns MARS_OK or a negative code; on error nothing is enqueued.
- * Calls that share a workspace must not overlap.
+ * Calls that share a workspace must not overlap.  Calls with workspaces (and outputs) of their
+ * own may run side by side on different streams: the library keeps no state, and the
+ * latency-bound per-request kernel of one call then runs beside the bandwidth-bound row
+ * reduction of another.
  */
 int mars_verify(const void* logits, int logits_dtype,
                 const int32_t* draft_tokens, const int32_t* tree_parent,

@@ -432,7 +432,7 @@ __device__ __forceinline__ void tile_find(const double* sh_tile, int n, int lane
 
 constexpr int kMaxGroupsPerRequest = 32;   // work-groups that may share one request
 constexpr float kClosedFormMinNorm = 0.1f; // one-hot residual: Z = 1 - f(x) is used when at least this
-constexpr int kResident = 4;               // groups of eight elements a thread can keep in registers
+constexpr int kResident = 3;               // groups of eight elements a thread can keep in registers
 
 // RESIDENT: every slice is at most kResident groups per thread (decided by the host from G and V).
 template <typename T, typename TQ, bool RESIDENT>

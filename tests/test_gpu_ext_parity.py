@@ -386,3 +386,31 @@ def test_margin_stats_many_cells_and_no_row_output():
     ref = mars_ref.margin_stats(w.logits, w.theta, w.temperature, ranges, bins)
     c = counts.cpu().numpy().view(np.uint32)
     assert np.array_equal(c[:bins[0] + 2], ref["hist_z1"]) and c[-4:].tolist() == ref["summary"].tolist()
+
+
+def test_calls_on_two_streams_with_their_own_workspaces_overlap_and_stay_exact():
+    # The library keeps no state: calls that do not share a workspace may run side by side.  Two different
+    # headline-shaped batches alternate on two streams (the per-request kernel of one call beside the row
+    # reduction of the next); after a burst of calls each stream's outputs equal the oracle's.
+    from oracle import screen
+    from paper_2601_15498_amd import binding as M
+    from tests.gpu_util import to_device
+    ws_list = [make_config(2, B=8), make_config(2, B=8, seed=92)]
+    refs = [screen.screen_uniforms(w) for w in ws_list]
+    devs = [to_device(w) for w in ws_list]
+    dev = devs[0]["logits"].device
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    wss = [M.alloc_workspace(w.B, w.N, w.V, dev) for w in ws_list]
+    outs = [M.VerifyOutputs(w.B, w.N, dev) for w in ws_list]
+    torch.cuda.synchronize()
+    for i in range(24):
+        j = i % 2
+        d = devs[j]
+        with torch.cuda.stream(streams[j]):
+            M.mars_verify(d["logits"], d["draft_tokens"], d["tree_parent"], d["theta"], ws_list[j].temperature,
+                          d["uniforms"], d["draft_probs"], outs[j], wss[j])
+    torch.cuda.synchronize()
+    for j in range(2):
+        assert (outs[j].request_status.cpu().numpy() == 0).all()
+        for key in ("accept_len", "bonus_token", "accept_mask", "path_idx", "decision"):
+            assert np.array_equal(getattr(outs[j], key).cpu().numpy(), refs[j][key]), (j, key)
