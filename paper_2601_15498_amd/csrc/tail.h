@@ -1,6 +1,7 @@
 // Per-request tail of the verification pass: merge the row partials, take the
 // per-node decisions, select the path and produce the correction / bonus token.
-// One work-group per request.
+// One work-group per request in greedy mode; in sampling mode up to 32 work-groups share a
+// request, each owning a slice of the vocabulary.
 //
 // Greedy mode is Algorithm 1 on a tree: local three-way test per node, reachability
 // by pointer jumping, deepest reachable node (lowest index on ties), token = v(1) of
