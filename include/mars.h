@@ -90,6 +90,9 @@ enum {
  * Only the logit ratio needs the positive-domain condition. */
 enum { MARS_IND_LOGIT_RATIO = 0, MARS_IND_PROB_RATIO = 1, MARS_IND_LOGIT_GAP = 2 };
 
+/* Parts of the pass (mars_verify_options.stages). */
+enum { MARS_STAGE_ROWS = 1, MARS_STAGE_REQUESTS = 2 };
+
 /* Most thresholds per request one call of mars_verify_ex sweeps. */
 #define MARS_MAX_THETAS 64
 
@@ -223,7 +226,15 @@ int mars_verify(const void* logits, int logits_dtype,
  *                 flags the request MARS_REQ_TIMEOUT and carries on (every wait in the library is
  *                 bounded).  0 = the default, on the order of a second.  Only of interest to
  *                 callers that share the GPU with other work, and to tests of that path.
- *   reserved      must be 0.
+ *   stages        which part of the pass the call enqueues: 0 or MARS_STAGE_ROWS | MARS_STAGE_REQUESTS = all of
+ *                 it; MARS_STAGE_ROWS = the row reduction only (it also clears what the second part
+ *                 accumulates into); MARS_STAGE_REQUESTS = the per-request part only, on a workspace the
+ *                 first part has filled (same arguments in both calls).  Splitting a pass lets a caller
+ *                 that overlaps passes on several streams put its own events between the parts: in
+ *                 sampling mode the work-groups of a request wait for each other and the per-request part
+ *                 of one pass holds up to one work-group per compute unit, so the per-request parts of
+ *                 overlapping passes should follow one another (an event recorded after one, waited for
+ *                 before the next) while row reductions may run beside them freely.
  *   out_tokens    device out, optional, [K,B,N] int32: the committed sequence V_out of Alg. 1 -- the
  *                 tokens of the accepted nodes in path order, then the correction / bonus token,
  *                 then -1.
@@ -238,7 +249,7 @@ typedef struct mars_verify_options {
   int32_t  indicator;
   int32_t  n_theta;
   int32_t  spin_limit;
-  int32_t  reserved;
+  int32_t  stages;
   int32_t* out_tokens;
   int32_t* out_len;
   int32_t* keep_rows;
@@ -257,7 +268,7 @@ size_t mars_workspace_bytes_ex(int B, int N, int V, int n_theta);
  * options == NULL is mars_verify.  n_theta * B requests are verified side by side, which in
  * sampling mode leaves fewer work-groups per request.  Errors as for mars_verify, plus
  * MARS_ERR_ARG for an unknown indicator, n_theta outside [0, MARS_MAX_THETAS], a negative
- * spin_limit, a non-zero reserved field, or some but not all of the four commit outputs.
+ * spin_limit, stages outside [0, 3], or some but not all of the four commit outputs.
  */
 int mars_verify_ex(const void* logits, int logits_dtype,
                    const int32_t* draft_tokens, const int32_t* tree_parent,

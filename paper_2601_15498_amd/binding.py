@@ -18,12 +18,13 @@ MARS_OK = 0
 MARS_MAX_NODES = 1024
 MARS_MAX_THETAS = 64
 MARS_IND_LOGIT_RATIO, MARS_IND_PROB_RATIO, MARS_IND_LOGIT_GAP = 0, 1, 2
+MARS_STAGE_ROWS, MARS_STAGE_REQUESTS = 1, 2
 
 
 class VerifyOptionsStruct(ctypes.Structure):
     """struct mars_verify_options (a host struct holding device pointers)."""
     _fields_ = [("indicator", ctypes.c_int32), ("n_theta", ctypes.c_int32),
-                ("spin_limit", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("spin_limit", ctypes.c_int32), ("stages", ctypes.c_int32),
                 ("out_tokens", ctypes.c_void_p), ("out_len", ctypes.c_void_p),
                 ("keep_rows", ctypes.c_void_p), ("keep_offsets", ctypes.c_void_p)]
 
@@ -211,7 +212,7 @@ def mars_verify_ex(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent
                    theta: torch.Tensor, temperature: float, uniforms: torch.Tensor = None,
                    draft_probs: torch.Tensor = None, out: VerifyOutputs = None, workspace: torch.Tensor = None,
                    indicator: int = MARS_IND_LOGIT_RATIO, n_theta: int = 1,
-                   want_commit: bool = False, spin_limit: int = 0) -> VerifyOutputs:
+                   want_commit: bool = False, spin_limit: int = 0, stages: int = 0) -> VerifyOutputs:
     """mars_verify with options: low-margin indicator, theta[K,B] swept in one pass, committed sequence and
     kept cache rows.  See include/mars.h."""
     B, N, V = logits.shape
@@ -231,7 +232,7 @@ def mars_verify_ex(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent
     assert out.n_theta == n_theta
     if workspace is None:
         workspace = alloc_workspace(B, N, V, dev, n_theta)
-    opt = VerifyOptionsStruct(int(indicator), int(n_theta), int(spin_limit), 0,
+    opt = VerifyOptionsStruct(int(indicator), int(n_theta), int(spin_limit), int(stages),
                               None if out.out_tokens is None else out.out_tokens.data_ptr(),
                               None if out.out_len is None else out.out_len.data_ptr(),
                               None if out.keep_rows is None else out.keep_rows.data_ptr(),

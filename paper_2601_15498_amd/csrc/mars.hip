@@ -212,13 +212,14 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
   using namespace mars;
   if (!logits || !draft_tokens || !tree_parent || !theta || !accept_mask || !accept_len || !path_idx || !bonus_token)
     return MARS_ERR_ARG;
-  int K = 1, indicator = MARS_IND_LOGIT_RATIO, spin_limit = 0;
+  int K = 1, indicator = MARS_IND_LOGIT_RATIO, spin_limit = 0, stages = MARS_STAGE_ROWS | MARS_STAGE_REQUESTS;
   int32_t *out_tokens = nullptr, *out_len = nullptr, *keep_rows = nullptr, *keep_offsets = nullptr;
   if (options) {
     K = options->n_theta == 0 ? 1 : options->n_theta;
     indicator = options->indicator;
     spin_limit = options->spin_limit;
-    if (spin_limit < 0 || options->reserved != 0) return MARS_ERR_ARG;
+    if (spin_limit < 0 || options->stages < 0 || options->stages > 3) return MARS_ERR_ARG;
+    if (options->stages != 0) stages = options->stages;
     out_tokens = options->out_tokens; out_len = options->out_len;
     keep_rows = options->keep_rows; keep_offsets = options->keep_offsets;
   }
@@ -247,8 +248,10 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
     clr.counters = reinterpret_cast<unsigned int*>(request_status);
     clr.ncounters = static_cast<long>(K) * B;
   }
-  if (launch_row_reduce(logits, logits_dtype, rows, V, L.splits, sampling, c, partials, clr, stream) != hipSuccess)
+  if ((stages & MARS_STAGE_ROWS) &&
+      launch_row_reduce(logits, logits_dtype, rows, V, L.splits, sampling, c, partials, clr, stream) != hipSuccess)
     return MARS_ERR_HIP;
+  if (!(stages & MARS_STAGE_REQUESTS)) return MARS_OK;
 
   TailArgs a;
   a.logits = logits; a.tok = draft_tokens; a.par = tree_parent;

@@ -115,7 +115,8 @@ def test_host_side_argument_errors_enqueue_nothing(lib):
     assert call_ex(VerifyOptionsStruct(0, 1, 0, 0, 0x1000, 0x1000, 0x1000, None)) == -1
     assert call_ex(VerifyOptionsStruct(1, 8, 0, 0, None, None, None, None), wsb=4096) == -3  # the sweep needs more workspace
     assert call_ex(VerifyOptionsStruct(0, 1, -5, 0, None, None, None, None)) == -1  # negative spin limit
-    assert call_ex(VerifyOptionsStruct(0, 1, 0, 7, None, None, None, None)) == -1   # reserved field set
+    assert call_ex(VerifyOptionsStruct(0, 1, 0, 7, None, None, None, None)) == -1   # unknown stages
+    assert call_ex(VerifyOptionsStruct(0, 1, 0, -1, None, None, None, None)) == -1
     ms = lib.mars_margin_stats
     rg = (ctypes.c_float * 6)(0, 1, 0, 1, 0, 1)
     bn = (ctypes.c_int32 * 3)(4, 4, 4)

@@ -414,3 +414,28 @@ def test_calls_on_two_streams_with_their_own_workspaces_overlap_and_stay_exact()
         assert (outs[j].request_status.cpu().numpy() == 0).all()
         for key in ("accept_len", "bonus_token", "accept_mask", "path_idx", "decision"):
             assert np.array_equal(getattr(outs[j], key).cpu().numpy(), refs[j][key]), (j, key)
+
+
+@pytest.mark.parametrize("T", [0.0, 0.7])
+def test_pass_enqueued_in_two_parts_equals_the_whole(T):
+    # stages: the row reduction and the per-request part as two calls with the same arguments, other work on
+    # the stream in between; the result is that of the single call, bit for bit.
+    from paper_2601_15498_amd import binding as M
+    from tests.gpu_util import to_device
+    w = make_config(2, B=5, temperature=T)
+    d = to_device(w)
+    dev = d["logits"].device
+    ws = M.alloc_workspace(w.B, w.N, w.V, dev)
+    args = (d["logits"], d["draft_tokens"], d["tree_parent"], d["theta"], T, d["uniforms"] if T > 0 else None,
+            d["draft_probs"] if T > 0 else None)
+    whole = M.mars_verify_ex(*args, workspace=ws, want_commit=True)
+    torch.cuda.synchronize()
+    parts = M.VerifyOutputs(w.B, w.N, dev, want_commit=True)
+    M.mars_verify_ex(*args, out=parts, workspace=ws, stages=M.MARS_STAGE_ROWS)
+    junk = torch.randn(1 << 20, device=dev).sum()          # unrelated work between the two parts
+    M.mars_verify_ex(*args, out=parts, workspace=ws, stages=M.MARS_STAGE_REQUESTS)
+    torch.cuda.synchronize()
+    assert torch.isfinite(junk)
+    for key in ("accept_len", "bonus_token", "accept_mask", "path_idx", "decision", "request_status", "stats", "diag",
+                "out_tokens", "out_len", "keep_rows", "keep_offsets"):
+        assert torch.equal(getattr(parts, key), getattr(whole, key)), key
