@@ -51,13 +51,13 @@ extern "C" {
 /* Element type of logits / draft_probs. */
 enum { MARS_F32 = 0, MARS_BF16 = 1 };
 
-/* Return codes (host-detectable errors enqueue nothing). */
+/* Return codes (argument, type and workspace errors are detected on the host and enqueue nothing). */
 enum {
   MARS_OK            = 0,
   MARS_ERR_ARG       = -1, /* null required pointer, B/N/V out of range, T < 0 or NaN */
   MARS_ERR_DTYPE     = -2, /* unknown element type */
   MARS_ERR_WORKSPACE = -3, /* workspace missing, misaligned or too small */
-  MARS_ERR_HIP       = -4  /* a HIP call (launch, attribute query) failed */
+  MARS_ERR_HIP       = -4  /* a kernel launch failed; kernels of the same call launched before it stay enqueued */
 };
 
 /* Per-request status written by the device (data-dependent problems). */
