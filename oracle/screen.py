@@ -30,13 +30,19 @@ def _sub(a, idx):
 
 
 def screen_uniforms(w, guard: float = 1e-4, min_norm: float = 2e-2, max_rounds: int = 200,
-                    seed: int = 987654321, cdf_guard: float = None, indicator: int = 0, thetas=None):
+                    seed: int = 987654321, cdf_guard: float = None, indicator: int = 0, thetas=None,
+                    drop_unscreenable: bool = False):
     """``w`` is a workload object with numpy fields (logits, draft_tokens, tree_parent, theta,
     temperature, uniforms, draft_probs); ``w.uniforms`` is updated in place.
 
     ``thetas`` [K,B] (optional) screens for a sweep: the same uniforms serve the K walks of a
     request, so a request is re-drawn until all K of them are clean; the outputs then carry a
-    leading axis of length K."""
+    leading axis of length K.
+
+    Some requests cannot be screened whatever is drawn (a peaked distribution whose residual mass stays
+    below ``min_norm`` on every path that is at all likely).  With ``drop_unscreenable`` they are given
+    up after ``max_rounds`` and flagged False in the returned ``"clean"`` mask [B] (their expected values
+    are not well posed and a caller leaves them out of its comparison); otherwise that raises."""
     th = np.asarray(w.theta, np.float32)[None] if thetas is None else np.asarray(thetas, np.float32)
     K = th.shape[0]
 
@@ -46,8 +52,12 @@ def screen_uniforms(w, guard: float = 1e-4, min_norm: float = 2e-2, max_rounds: 
                                 th[k] if idx is None else th[k][idx], w.temperature, pick(w.uniforms),
                                 pick(w.draft_probs), indicator) for k in range(K)]
 
+    clean = np.ones(w.logits.shape[0], bool)
+
     def result(outs):
-        return outs[0] if thetas is None else {key: np.stack([o[key] for o in outs]) for key in outs[0]}
+        r = outs[0] if thetas is None else {key: np.stack([o[key] for o in outs]) for key in outs[0]}
+        r["clean"] = clean
+        return r
 
     outs = run()
     if not w.temperature > 0:
@@ -60,12 +70,15 @@ def screen_uniforms(w, guard: float = 1e-4, min_norm: float = 2e-2, max_rounds: 
         for o in outs:
             d = o["diag"]
             dirty |= (d["min_accept_margin"] < guard) | (d["min_cdf_margin"] < cdf_guard) | (d["min_norm"] < min_norm)
-        bad = np.nonzero(dirty)[0]
+        bad = np.nonzero(dirty & clean)[0]
         if bad.size == 0:
             return result(outs)
         rounds += 1
         if rounds > max_rounds:
-            raise RuntimeError(f"uniform guard band not reached for requests {bad.tolist()}")
+            if not drop_unscreenable:
+                raise RuntimeError(f"uniform guard band not reached for requests {bad.tolist()}")
+            clean[bad] = False
+            return result(outs)
         for b in bad:
             rng = np.random.default_rng(np.random.SeedSequence([seed, rounds, int(b)]))
             w.uniforms[b] = rng.random(w.uniforms.shape[1], dtype=np.float32)

@@ -251,3 +251,13 @@ def test_rows_not_16_byte_aligned_base():
     torch.cuda.synchronize()
     from tests.gpu_util import assert_stats_match
     assert_stats_match(st, mars_ref.row_stats(z, 0.9, 1.0), True, "misaligned_base")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B", [3, 40])
+def test_draft_distribution_stored_as_bf16(dtype, B):
+    # every combination of logits and draft-distribution storage, in the register-resident form of the
+    # sampling kernel (few requests, many work-groups each) and in the streaming form (many requests)
+    w = make_config(2, B=B, N=20, V=40008, dtype=dtype, tree={"kind": "tree", "depth": 4, "max_children": 3})
+    w.draft_probs = f32_to_bf16_bits(w.draft_probs)
+    compare(w, label=f"bf16_q_{dtype}_B{B}", cdf_guard=5e-6, drop_unscreenable=True)
