@@ -439,3 +439,39 @@ def test_pass_enqueued_in_two_parts_equals_the_whole(T):
     for key in ("accept_len", "bonus_token", "accept_mask", "path_idx", "decision", "request_status", "stats", "diag",
                 "out_tokens", "out_len", "keep_rows", "keep_offsets"):
         assert torch.equal(getattr(parts, key), getattr(whole, key)), key
+
+
+def test_strict_sampling_on_the_gpu_reproduces_the_target_distribution():
+    # Not through the oracle: with theta > 1 the pass is plain speculative sampling, which is lossless
+    # (Sec. 2.3): whatever the draft distribution, the first committed token follows softmax(z / T).
+    # 40 000 requests share one root row and one draft distribution; each draws its own draft token from
+    # q and its own uniforms.  Chi-square against the closed form, and the same test must reject the
+    # draft distribution itself.
+    from scipy.stats import chi2
+    from paper_2601_15498_amd import binding as M
+    rng = np.random.default_rng(31)
+    B, N, V, T = 40000, 2, 6, 0.8
+    z0 = np.array([2.0, 1.2, 0.1, -0.5, 1.7, -2.0], np.float32)
+    z1 = rng.normal(0, 1, V).astype(np.float32)
+    q0 = np.array([0.05, 0.4, 0.2, 0.05, 0.1, 0.2], np.float32)
+    p = np.exp(z0.astype(np.float64) / np.float64(np.float32(T)))
+    p /= p.sum()
+    z = np.tile(np.stack([z0, z1])[None], (B, 1, 1))
+    q = np.tile(np.stack([q0, np.full(V, 1.0 / V, np.float32)])[None], (B, 1, 1)).astype(np.float32)
+    tok = np.zeros((B, N), np.int32)
+    qn = q0.astype(np.float64) / q0.astype(np.float64).sum()
+    tok[:, 1] = rng.choice(V, size=B, p=qn)
+    par = np.tile(np.array([-1, 0], np.int32), (B, 1))
+    u = rng.random((B, N + 1), dtype=np.float32)
+    dev = torch.device("cuda:0")
+    out = M.mars_verify_ex(torch.from_numpy(z).to(dev), torch.from_numpy(tok).to(dev), torch.from_numpy(par).to(dev),
+                           torch.full((B,), 2.0, dtype=torch.float32, device=dev), T, torch.from_numpy(u).to(dev),
+                           torch.from_numpy(q).to(dev), want_commit=True)
+    torch.cuda.synchronize()
+    first = out.out_tokens[:, 0].cpu().numpy()
+    counts = np.bincount(first, minlength=V).astype(np.float64)
+    stat = ((counts - B * p) ** 2 / (B * p)).sum()
+    limit = chi2.ppf(1 - 1e-4, V - 1)
+    say(f"[info] first committed token: chi2 {stat:.2f} (limit {limit:.2f}), accepted {float(out.accept_len.float().mean()):.3f}")
+    assert stat < limit
+    assert ((counts - B * qn) ** 2 / (B * qn)).sum() > 10 * limit
