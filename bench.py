@@ -58,9 +58,9 @@ WORKLOADS = {
 }
 
 
-def kernel_source_digest() -> str:
+def kernel_source_digest(files=("common.h", "row_reduce.h")) -> str:
     h = hashlib.sha256()
-    for f in ("common.h", "row_reduce.h"):
+    for f in files:
         with open(os.path.join(ROOT, "paper_2601_15498_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]
@@ -78,6 +78,19 @@ def measured_traffic():
     if t.get("kernel_source_digest") != kernel_source_digest():
         return None
     return t.get("hbm_bytes_per_launch")
+
+
+def measured_pass_traffic():
+    """HBM bytes of a whole pass on the headline workload (row reduction + per-request kernel) from the
+    same counter runs, or None when either kernel's source has changed since."""
+    k1 = measured_traffic()
+    if k1 is None:
+        return None
+    with open(os.path.join(ROOT, "profiles", "row_reduce_cfg2_traffic.json")) as fh:
+        t = json.load(fh)
+    if t.get("tail_source_digest") != kernel_source_digest(("common.h", "tail.h")) or "tail_hbm_bytes_per_launch" not in t:
+        return None
+    return k1 + t["tail_hbm_bytes_per_launch"]
 
 
 def main() -> int:
@@ -243,6 +256,8 @@ def main() -> int:
                    "single_stream_ms_per_step": single_elapsed / args.steps * 1e3,
                    "single_stream_rows_per_s": rows * args.steps / single_elapsed,
                    "whole_pass_logits_GBps": rows * V * elt / (ms_per_step * 1e-3) / 1e9,
+                   "single_stream_pass_hbm_GBps": (measured_pass_traffic() / (single_elapsed / args.steps) / 1e9
+                                                   if wl == "headline" and measured_pass_traffic() else None),
                    "call_us_p10": pct[10], "call_us_median": pct[50], "call_us_p90": pct[90],
                    "input_generation_s": round(t_gen, 1)},
         "roofline": {"bound": "hbm", "kernel": k1_name,
