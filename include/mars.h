@@ -316,6 +316,34 @@ int mars_margin_stats(const void* logits, int logits_dtype, const float* theta, 
                       mars_margin_row* rows_out, uint32_t* counts,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Greedy verification straight from the target model's last hidden states (Eq. 2: the logits of a
+ * row are z = W h): the LM-head product and the top-2 identification of Sec. 3.3 run in one
+ * kernel on the matrix cores, and the logits are never written to memory.  The logits are
+ * defined as the fp32-accumulated products rounded once to bf16 (what a bf16 LM head hands to the
+ * verifier); everything behind them -- low-margin test, Alg. 1 on a chain or tree, committed
+ * sequence, sweep over thresholds -- is mars_verify_ex in greedy mode.
+ *
+ *   hidden   device, [B,N,H] bf16, 16-byte aligned: last hidden state of every node.
+ *   weight   device, [V,H] bf16, 16-byte aligned: the LM head, one row per vocabulary entry.
+ *   H        hidden size, a multiple of 64.
+ *   theta, draft_tokens, tree_parent, outputs, options: as for mars_verify_ex with temperature 0
+ *            (request_status, decision, stats optional; options may be NULL).
+ *   workspace device, 256-byte aligned, >= mars_lmhead_workspace_bytes(B,N,V,H,n_theta).
+ * Returns MARS_OK or a negative code; MARS_ERR_ARG also for H not a multiple of 64 or misaligned
+ * hidden / weight.  On MARS_ERR_HIP kernels launched before the failing one stay enqueued;
+ * otherwise an error enqueues nothing.  Calls with workspaces of their own may overlap.
+ */
+size_t mars_lmhead_workspace_bytes(int B, int N, int V, int H, int n_theta);
+int mars_lmhead_verify(const void* hidden, const void* weight, int H,
+                       const int32_t* draft_tokens, const int32_t* tree_parent, const float* theta,
+                       int B, int N, int V,
+                       uint8_t* accept_mask, int32_t* accept_len, int32_t* path_idx,
+                       int32_t* bonus_token, uint8_t* decision, int32_t* request_status,
+                       mars_row_stat* stats,
+                       void* workspace, size_t workspace_bytes, void* hip_stream,
+                       const mars_verify_options* options);
+
 #ifdef __cplusplus
 }
 #endif

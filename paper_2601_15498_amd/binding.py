@@ -70,6 +70,14 @@ def lib():
                                         ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32),
                                         ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.mars_lmhead_workspace_bytes.restype = ctypes.c_size_t
+        L.mars_lmhead_workspace_bytes.argtypes = [ctypes.c_int] * 5
+        L.mars_lmhead_verify.restype = ctypes.c_int
+        L.mars_lmhead_verify.argtypes = ([ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+                                         + [ctypes.c_void_p] * 7
+                                         + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                            ctypes.POINTER(VerifyOptionsStruct)])
         _lib = L
     return _lib
 
@@ -275,3 +283,42 @@ def mars_margin_stats(logits: torch.Tensor, theta: torch.Tensor, temperature: fl
                                    rg, bn, _ptr(rows_out), _ptr(counts), _ptr(workspace), workspace.numel(),
                                    _stream()))
     return rows_out, counts
+
+
+def mars_lmhead_workspace_bytes(B: int, N: int, V: int, H: int, n_theta: int = 1) -> int:
+    return int(lib().mars_lmhead_workspace_bytes(B, N, V, H, n_theta))
+
+
+def mars_lmhead_verify(hidden: torch.Tensor, weight: torch.Tensor, draft_tokens: torch.Tensor,
+                       tree_parent: torch.Tensor, theta: torch.Tensor, out: VerifyOutputs = None,
+                       workspace: torch.Tensor = None, indicator: int = MARS_IND_LOGIT_RATIO, n_theta: int = 1,
+                       want_commit: bool = False) -> VerifyOutputs:
+    """Greedy verification from the last hidden states [B,N,H] and the LM-head weight [V,H] (both bf16, or
+    their bit patterns): the logits are formed, reduced and dropped inside one kernel.  See include/mars.h."""
+    B, N, H = hidden.shape
+    V = weight.shape[0]
+    dev = hidden.device
+    assert hidden.is_contiguous() and weight.is_contiguous() and weight.shape == (V, H)
+    assert _dtype_code(hidden) == MARS_BF16 and _dtype_code(weight) == MARS_BF16
+    assert draft_tokens.dtype == torch.int32 and draft_tokens.shape == (B, N) and draft_tokens.is_contiguous()
+    assert tree_parent.dtype == torch.int32 and tree_parent.shape == (B, N) and tree_parent.is_contiguous()
+    assert theta.dtype == torch.float32 and theta.numel() == n_theta * B and theta.is_contiguous()
+    if out is None:
+        out = VerifyOutputs(B, N, dev, want_diag=False, n_theta=n_theta, want_commit=want_commit)
+    assert out.n_theta == n_theta
+    if workspace is None:
+        n = mars_lmhead_workspace_bytes(B, N, V, H, n_theta)
+        if n == 0:
+            raise MarsError(f"sizes out of range: B={B} N={N} V={V} H={H} n_theta={n_theta}")
+        workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+    opt = VerifyOptionsStruct(int(indicator), int(n_theta), 0, 0,
+                              None if out.out_tokens is None else out.out_tokens.data_ptr(),
+                              None if out.out_len is None else out.out_len.data_ptr(),
+                              None if out.keep_rows is None else out.keep_rows.data_ptr(),
+                              None if out.keep_offsets is None else out.keep_offsets.data_ptr())
+    _check(lib().mars_lmhead_verify(_ptr(hidden), _ptr(weight), H, _ptr(draft_tokens), _ptr(tree_parent), _ptr(theta),
+                                    B, N, V, _ptr(out.accept_mask), _ptr(out.accept_len), _ptr(out.path_idx),
+                                    _ptr(out.bonus_token), _ptr(out.decision), _ptr(out.request_status),
+                                    _ptr(out.stats), _ptr(workspace), workspace.numel(), _stream(),
+                                    ctypes.byref(opt)))
+    return out

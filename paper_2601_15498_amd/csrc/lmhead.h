@@ -1,0 +1,196 @@
+// LM head fused with the row reduction (paper Eq. 2, z = W h, followed by the top-2
+// identification of Sec. 3.3): the logits of a tile are formed on the matrix cores, rounded to
+// bf16 in registers, reduced to each row's two largest (value desc, index asc) and dropped --
+// they are never written to memory.  Output: partial results in the format of the streaming row
+// reduction, so that the per-request kernels behind it are the same.
+//
+// A work-group owns a slab of BM hidden-state rows and a contiguous run of vocabulary tiles
+// (256 entries each).  Per tile it walks the hidden dimension in slabs of 64: both operands are
+// staged through LDS (double-buffered, one barrier per slab), four waves in a 2 x 2 arrangement
+// each accumulate (BM/2) x 128 logits with v_mfma_f32_32x32x16_bf16.  The weight rows are the
+// first MFMA operand and the hidden states the second, so that a lane ends up holding, for one
+// hidden-state row, 16 vocabulary entries per accumulator block: the row's top-2 over the wave's
+// 128 entries is taken inside the lane, the two halves of the wave that share a row meet once at
+// the very end, and a running pair per row is carried across the tiles of the run.
+#pragma once
+
+#include "common.h"
+
+namespace mars {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kLmThreads = 256;           // 4 waves: 2 (hidden rows) x 2 (vocabulary)
+constexpr int kLmBN = 256;                // vocabulary entries per tile
+constexpr int kLmBK = 64;                 // hidden-state elements per staged slab
+constexpr int kLmStride = kLmBK + 8;      // LDS row stride in elements: 144 bytes, conflict-free 16-byte reads
+constexpr int kLmChunks = kLmBK / 8;      // 16-byte chunks per staged row
+constexpr int kLmMaxBM = 192;             // tallest slab of hidden-state rows (256 no longer fits the register file)
+
+// Order-preserving 16-bit pattern of a bf16 value (larger value = larger pattern).
+__device__ __forceinline__ uint32_t ord16(uint32_t u) { return (u & 0x8000u) ? (~u & 0xFFFFu) : (u | 0x8000u); }
+__device__ __forceinline__ uint32_t unord16(uint32_t o) { return (o & 0x8000u) ? (o & 0x7FFFu) : (~o & 0xFFFFu); }
+
+// fp32 -> bf16, round to nearest even (finite inputs), as a 16-bit pattern.
+__device__ __forceinline__ uint32_t bf16_rne(float x) {
+  const uint32_t u = __float_as_uint(x + 0.0f);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Staging of one operand slab: n 16-byte chunks per thread, rows 32 apart.
+template <int n>
+__device__ __forceinline__ void lm_load_global(u32x4 (&g)[n], const bf16_t* __restrict__ base,
+                                               const unsigned int (&off)[n], int k) {
+#pragma unroll
+  for (int i = 0; i < n; ++i) g[i] = *reinterpret_cast<const u32x4*>(base + off[i] + k);
+}
+template <int n>
+__device__ __forceinline__ void lm_store_lds(const u32x4 (&g)[n], bf16_t* first) {
+#pragma unroll
+  for (int i = 0; i < n; ++i) *reinterpret_cast<u32x4*>(first + i * 32 * kLmStride) = g[i];
+}
+
+template <int BM>
+__global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t* __restrict__ hidden,
+                                                                   const bf16_t* __restrict__ weight, int M, int V,
+                                                                   int H, int slabs, int tiles_n, int tiles_per_run,
+                                                                   int runs, Partial* __restrict__ partials) {
+  constexpr int WM = BM / 2;      // hidden-state rows per wave
+  constexpr int IB = WM / 32;     // 32-row blocks per wave
+  constexpr int JB = 4;           // 32-entry vocabulary blocks per wave (128 entries)
+  constexpr int A_LOADS = BM * kLmChunks / kLmThreads;      // 16-byte loads per thread and slab, hidden states
+  constexpr int W_LOADS = kLmBN * kLmChunks / kLmThreads;   // ... weight rows
+  static_assert(BM % 64 == 0 && BM >= 64 && BM <= kLmMaxBM, "slab height");
+
+  __shared__ __attribute__((aligned(16))) bf16_t sh_a[2][BM][kLmStride];
+  __shared__ __attribute__((aligned(16))) bf16_t sh_w[2][kLmBN][kLmStride];
+
+  // Work-groups of one run (all slabs) sit on the same die (block index mod 8) next to each
+  // other in launch order: they read the same weight tiles at the same time.
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int slab = local % slabs, run = (local / slabs) * 8 + xcd;
+  if (run >= runs) return;
+  const int m0 = slab * BM;
+  const int tile_begin = run * tiles_per_run, tile_end = min(tiles_n, tile_begin + tiles_per_run);
+
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int wn = wave & 1, wm = wave >> 1;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int KT = H / kLmBK;
+
+  // What this thread stages per slab of 64: 16-byte chunk tid%8 of rows tid/8, tid/8 + 32, ...
+  // of the tile (rows past the end are clamped to the last valid row; their values are never
+  // used).  Tile base pointers are uniform, the offsets inside a tile fit 32 bits.
+  const int srow = tid / kLmChunks, schunk = (tid % kLmChunks) * 8;
+  const bf16_t* __restrict__ a_tile = hidden + static_cast<size_t>(m0) * H;
+  unsigned int a_off[A_LOADS];
+#pragma unroll
+  for (int i = 0; i < A_LOADS; ++i)
+    a_off[i] = static_cast<unsigned int>(min(M - 1 - m0, srow + i * 32)) * H + schunk;
+
+  unsigned long long best1[IB], best2[IB];
+#pragma unroll
+  for (int ib = 0; ib < IB; ++ib) { best1[ib] = 0ull; best2[ib] = 0ull; }
+
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const int n0 = tile * kLmBN;
+    const bf16_t* __restrict__ w_tile = weight + static_cast<size_t>(n0) * H;
+    unsigned int w_off[W_LOADS];
+#pragma unroll
+    for (int i = 0; i < W_LOADS; ++i)
+      w_off[i] = static_cast<unsigned int>(min(V - 1 - n0, srow + i * 32)) * H + schunk;
+
+    f32x16_t acc[JB][IB];
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+      for (int ib = 0; ib < IB; ++ib)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[jb][ib][r] = 0.0f;
+
+    u32x4 ga[A_LOADS], gw[W_LOADS];
+    // (the previous tile ended with a barrier behind its last LDS reads)
+    lm_load_global<A_LOADS>(ga, a_tile, a_off, 0);
+    lm_load_global<W_LOADS>(gw, w_tile, w_off, 0);
+    lm_store_lds<A_LOADS>(ga, &sh_a[0][srow][schunk]);
+    lm_store_lds<W_LOADS>(gw, &sh_w[0][srow][schunk]);
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+      const int cur = kt & 1;
+      if (kt + 1 < KT) {  // in flight while this slab is multiplied
+        lm_load_global<A_LOADS>(ga, a_tile, a_off, (kt + 1) * kLmBK);
+        lm_load_global<W_LOADS>(gw, w_tile, w_off, (kt + 1) * kLmBK);
+      }
+#pragma unroll
+      for (int ks = 0; ks < kLmBK / 16; ++ks) {
+        // lane l supplies row l%32 of its block, elements 8*(l/32) .. +7 of the 16-deep step
+        u32x4 wf[JB], hf[IB];
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb)
+          wf[jb] = *reinterpret_cast<const u32x4*>(&sh_w[cur][wn * 128 + jb * 32 + l32][ks * 16 + half * 8]);
+#pragma unroll
+        for (int ib = 0; ib < IB; ++ib)
+          hf[ib] = *reinterpret_cast<const u32x4*>(&sh_a[cur][wm * WM + ib * 32 + l32][ks * 16 + half * 8]);
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+          for (int ib = 0; ib < IB; ++ib)
+            acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[jb]),
+                                                                  __builtin_bit_cast(bf16x8_t, hf[ib]), acc[jb][ib], 0, 0, 0);
+      }
+      if (kt + 1 < KT) {
+        lm_store_lds<A_LOADS>(ga, &sh_a[cur ^ 1][srow][schunk]);
+        lm_store_lds<W_LOADS>(gw, &sh_w[cur ^ 1][srow][schunk]);
+      }
+      __syncthreads();
+    }
+
+    // The tile's logits, in this lane: hidden-state row m0 + wm*WM + ib*32 + l32, vocabulary entries
+    // n0 + wn*128 + jb*32 + 8*(r/4) + 4*half + r%4.  Round to bf16, take the top-2 of the 16*JB
+    // entries per row block with 32-bit keys (pattern << 16 | 127 - entry: larger value first, then
+    // the lower entry; `half` is the same for all of a lane's entries and is added afterwards).
+    const int nbase = n0 + wn * 128 + 4 * half;
+    const bool ragged = n0 + kLmBN > V;
+#pragma unroll
+    for (int ib = 0; ib < IB; ++ib) {
+      uint32_t k1 = 0u, k2 = 0u;
+#pragma unroll
+      for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int e = jb * 32 + 8 * (r / 4) + (r % 4);
+          uint32_t key = (ord16(bf16_rne(acc[jb][ib][r])) << 16) | static_cast<uint32_t>(127 - e);
+          if (ragged && nbase + e >= V) key = 0u;
+          const uint32_t lo = min(k1, key);
+          k1 = max(k1, key);
+          k2 = max(k2, lo);
+        }
+      if (k1 != 0u) top2_insert(best1[ib], best2[ib],
+                                make_key(__uint_as_float(unord16(k1 >> 16) << 16), nbase + 127 - static_cast<int>(k1 & 0x7Fu)));
+      if (k2 != 0u) top2_insert(best1[ib], best2[ib],
+                                make_key(__uint_as_float(unord16(k2 >> 16) << 16), nbase + 127 - static_cast<int>(k2 & 0x7Fu)));
+    }
+  }
+
+  // Lanes l and l + 32 hold the same rows (different vocabulary entries): combine, and the lower
+  // half writes the partial result of (row, run, wave column).
+  const int parts = runs * 2;
+#pragma unroll
+  for (int ib = 0; ib < IB; ++ib) {
+    const unsigned long long o1 = __shfl_xor(best1[ib], 32, kWave), o2 = __shfl_xor(best2[ib], 32, kWave);
+    unsigned long long k1 = best1[ib], k2 = best2[ib];
+    top2_insert(k1, k2, o1);
+    top2_insert(k1, k2, o2);
+    const int row = m0 + wm * WM + ib * 32 + l32;
+    if (half == 0 && row < M) {
+      Partial out;
+      out.z1 = neg_inf(); out.id1 = -1; out.z2 = neg_inf(); out.id2 = -1; out.s = 0.0f; out.ref = 0.0f;
+      if (k1 != 0ull) { out.z1 = key_value(k1); out.id1 = key_index(k1); }
+      if (k2 != 0ull) { out.z2 = key_value(k2); out.id2 = key_index(k2); }
+      partials[static_cast<size_t>(row) * parts + run * 2 + wn] = out;
+    }
+  }
+}
+
+}  // namespace mars

@@ -9,6 +9,7 @@
 #include "common.h"
 #include "row_reduce.h"
 #include "tail.h"
+#include "lmhead.h"
 
 namespace mars {
 
@@ -120,6 +121,50 @@ static ClearArgs clear_args(char* ws, const Layout& L, int B, int N, int K) {
   clr.N = N; clr.B = B; clr.xwords = 2 * L.G; clr.copies = K;
   clr.counters = nullptr; clr.ncounters = 0;
   return clr;
+}
+
+// ---------------------------------------------------------------- LM head fused with the row reduction
+// Slab height: the one that pads the fewest rows (the taller one on a tie: more reuse of the
+// weight tile).  Runs of vocabulary tiles: about one work-group per compute unit in all, so the
+// whole grid is resident at once and every work-group has the same amount of work.
+struct LmPlan {
+  int bm, slabs, tiles_n, tiles_per_run, runs, parts;
+};
+static LmPlan lm_plan(long rows, int V) {
+  LmPlan p;
+  long best = -1;
+  p.bm = 64;
+  for (int bm = 64; bm <= kLmMaxBM; bm += 64) {
+    const long padded = (rows + bm - 1) / bm * bm;
+    if (best < 0 || padded <= best) { best = padded; p.bm = bm; }
+  }
+  p.slabs = static_cast<int>((rows + p.bm - 1) / p.bm);
+  p.tiles_n = (V + kLmBN - 1) / kLmBN;
+  int want = kComputeUnits / p.slabs;
+  if (want < 1) want = 1;
+  if (want > p.tiles_n) want = p.tiles_n;
+  p.tiles_per_run = (p.tiles_n + want - 1) / want;
+  p.runs = (p.tiles_n + p.tiles_per_run - 1) / p.tiles_per_run;
+  p.parts = 2 * p.runs;
+  return p;
+}
+
+struct LmLayout {
+  LmPlan plan;
+  size_t partials_off, stats_off, total;
+};
+static LmLayout lm_layout(int B, int N, int V, int K) {
+  LmLayout L;
+  const long rows = static_cast<long>(B) * N;
+  L.plan = lm_plan(rows, V);
+  L.partials_off = 0;
+  L.stats_off = align_up(static_cast<size_t>(rows) * L.plan.parts * sizeof(Partial));
+  L.total = L.stats_off + align_up(static_cast<size_t>(K) * rows * sizeof(mars_row_stat));
+  return L;
+}
+
+static bool lm_sizes_ok(int B, int N, int V, int H, int K) {
+  return sizes_ok(B, N, V, K) && H >= kLmBK && H % kLmBK == 0 && static_cast<long>(B) * N <= (1L << 22);
 }
 
 }  // namespace mars
@@ -340,6 +385,80 @@ int mars_margin_stats(const void* logits, int logits_dtype, const float* theta, 
   hipLaunchKernelGGL(margin_stats_kernel, dim3(static_cast<unsigned int>((rows + 15) / 16)), dim3(256), 0, stream,
                      partials, static_cast<int>(rows), N, L.splits * kPartsPerItem, theta, indicator_scale(temperature),
                      hs, rows_out, counts);
+  return hipGetLastError() == hipSuccess ? MARS_OK : MARS_ERR_HIP;
+}
+
+size_t mars_lmhead_workspace_bytes(int B, int N, int V, int H, int n_theta) {
+  const int K = n_theta == 0 ? 1 : n_theta;
+  if (!mars::lm_sizes_ok(B, N, V, H, K)) return 0;
+  return mars::lm_layout(B, N, V, K).total;
+}
+
+int mars_lmhead_verify(const void* hidden, const void* weight, int H, const int32_t* draft_tokens,
+                       const int32_t* tree_parent, const float* theta, int B, int N, int V, uint8_t* accept_mask,
+                       int32_t* accept_len, int32_t* path_idx, int32_t* bonus_token, uint8_t* decision,
+                       int32_t* request_status, mars_row_stat* stats, void* workspace, size_t workspace_bytes,
+                       void* hip_stream, const mars_verify_options* options) {
+  using namespace mars;
+  if (!hidden || !weight || !draft_tokens || !tree_parent || !theta || !accept_mask || !accept_len || !path_idx ||
+      !bonus_token)
+    return MARS_ERR_ARG;
+  if (reinterpret_cast<uintptr_t>(hidden) % 16 != 0 || reinterpret_cast<uintptr_t>(weight) % 16 != 0)
+    return MARS_ERR_ARG;
+  int K = 1, indicator = MARS_IND_LOGIT_RATIO;
+  int32_t *out_tokens = nullptr, *out_len = nullptr, *keep_rows = nullptr, *keep_offsets = nullptr;
+  if (options) {
+    K = options->n_theta == 0 ? 1 : options->n_theta;
+    indicator = options->indicator;
+    if (options->spin_limit < 0 || options->stages < 0 || options->stages > 3) return MARS_ERR_ARG;
+    if (options->stages != 0 && options->stages != (MARS_STAGE_ROWS | MARS_STAGE_REQUESTS)) return MARS_ERR_ARG;
+    out_tokens = options->out_tokens; out_len = options->out_len;
+    keep_rows = options->keep_rows; keep_offsets = options->keep_offsets;
+  }
+  if (indicator != MARS_IND_LOGIT_RATIO && indicator != MARS_IND_PROB_RATIO && indicator != MARS_IND_LOGIT_GAP)
+    return MARS_ERR_ARG;
+  const int given = (out_tokens != nullptr) + (out_len != nullptr) + (keep_rows != nullptr) + (keep_offsets != nullptr);
+  if (given != 0 && given != 4) return MARS_ERR_ARG;
+  if (!lm_sizes_ok(B, N, V, H, K)) return MARS_ERR_ARG;
+  const LmLayout L = lm_layout(B, N, V, K);
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0 || workspace_bytes < L.total)
+    return MARS_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int rows = B * N;
+  char* ws = static_cast<char*>(workspace);
+  Partial* partials = reinterpret_cast<Partial*>(ws + L.partials_off);
+  const LmPlan& p = L.plan;
+
+  const dim3 grid(static_cast<unsigned int>(8 * p.slabs * ((p.runs + 7) / 8))), block(kLmThreads);
+  const bf16_t* hp = static_cast<const bf16_t*>(hidden);
+  const bf16_t* wp = static_cast<const bf16_t*>(weight);
+#define MARS_LM_LAUNCH(BM)                                                                                      \
+  hipLaunchKernelGGL((lmhead_reduce_kernel<BM>), grid, block, 0, stream, hp, wp, rows, V, H, p.slabs, p.tiles_n, \
+                     p.tiles_per_run, p.runs, partials)
+  switch (p.bm) {
+    case 64: MARS_LM_LAUNCH(64); break;
+    case 128: MARS_LM_LAUNCH(128); break;
+    default: MARS_LM_LAUNCH(192); break;
+  }
+#undef MARS_LM_LAUNCH
+  if (hipGetLastError() != hipSuccess) return MARS_ERR_HIP;
+
+  TailArgs a;
+  a.logits = nullptr; a.tok = draft_tokens; a.par = tree_parent; a.dprobs = nullptr;
+  a.theta = theta; a.u = nullptr; a.partials = partials;
+  a.stats = stats;
+  a.stats_ws = reinterpret_cast<mars_row_stat*>(ws + L.stats_off);
+  a.G = 1; a.spin_limit = 0; a.xslots = nullptr;
+  a.mask = accept_mask; a.len = accept_len; a.path = path_idx; a.bonus = bonus_token;
+  a.dec = decision; a.status = request_status; a.diag = nullptr;
+  a.B = K * B; a.Bd = B; a.N = N; a.V = V; a.splits = p.parts; a.c = 0.0f;
+  a.ind.kind = indicator; a.ind.cind = indicator_scale(0.0f);
+  a.out_tok = out_tokens; a.out_len = out_len;
+  hipLaunchKernelGGL(tail_greedy_kernel, dim3(static_cast<unsigned int>(K * B)), dim3(kGreedyThreads), 0, stream, a);
+  if (hipGetLastError() != hipSuccess) return MARS_ERR_HIP;
+  if (!keep_rows) return MARS_OK;
+  hipLaunchKernelGGL(compact_keep_kernel, dim3(static_cast<unsigned int>(K)), dim3(kKeepThreads), 0, stream, out_len,
+                     path_idx, B, N, keep_rows, keep_offsets);
   return hipGetLastError() == hipSuccess ? MARS_OK : MARS_ERR_HIP;
 }
 
