@@ -26,6 +26,7 @@ constexpr int kLmBN = 256;                // vocabulary entries per tile
 constexpr int kLmBK = 64;                 // hidden-state elements per staged slab
 constexpr int kLmStride = kLmBK + 8;      // LDS row stride in elements: 144 bytes, conflict-free 16-byte reads
 constexpr int kLmChunks = kLmBK / 8;      // 16-byte chunks per staged row
+constexpr int kLmDepth = 2;               // steps between the request of an operand slab and its use
 constexpr int kLmMaxBM = 192;             // tallest slab of hidden-state rows (256 no longer fits the register file)
 
 // Order-preserving 16-bit pattern of a bf16 value (larger value = larger pattern).
@@ -49,6 +50,13 @@ template <int n>
 __device__ __forceinline__ void lm_store_lds(const u32x4 (&g)[n], bf16_t* first) {
 #pragma unroll
   for (int i = 0; i < n; ++i) *reinterpret_cast<u32x4*>(first + i * 32 * kLmStride) = g[i];
+}
+
+// n operand fragments (16 bytes per lane each) of rows 32 apart.
+template <int n>
+__device__ __forceinline__ void lm_load_frags(u32x4 (&f)[n], const bf16_t* first) {
+#pragma unroll
+  for (int i = 0; i < n; ++i) f[i] = *reinterpret_cast<const u32x4*>(first + i * 32 * kLmStride);
 }
 
 template <int BM>
@@ -93,14 +101,49 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
 #pragma unroll
   for (int ib = 0; ib < IB; ++ib) { best1[ib] = 0ull; best2[ib] = 0ull; }
 
-  for (int tile = tile_begin; tile < tile_end; ++tile) {
-    const int n0 = tile * kLmBN;
-    const bf16_t* __restrict__ w_tile = weight + static_cast<size_t>(n0) * H;
-    unsigned int w_off[W_LOADS];
+  // The run is one sequence of steps (tile, slab of 64) whose operand requests do not stop at
+  // tile boundaries.  A step's operands are requested kLmDepth steps ahead into one of kLmDepth
+  // register sets -- a weight line comes from HBM, microseconds away under load, while a step's
+  // multiplications take well under one -- and pass through LDS one step ahead of their use.
+  // (KT is a multiple of kLmDepth, so every tile starts with register set 0.)
+  constexpr int D = kLmDepth;
+  u32x4 ga[D][A_LOADS], gw[D][W_LOADS];
+  int l_kt = 0, l_tile = tile_begin;  // the step the next request is for
+  const bf16_t* __restrict__ w_tile = weight + static_cast<size_t>(l_tile) * kLmBN * H;
+  unsigned int w_off[W_LOADS];
 #pragma unroll
-    for (int i = 0; i < W_LOADS; ++i)
-      w_off[i] = static_cast<unsigned int>(min(V - 1 - n0, srow + i * 32)) * H + schunk;
+  for (int i = 0; i < W_LOADS; ++i)
+    w_off[i] = static_cast<unsigned int>(min(V - 1 - l_tile * kLmBN, srow + i * 32)) * H + schunk;
 
+  // (Unconditional on purpose: with a request under a branch the compiler has to place its
+  // s_waitcnt for the case that nothing was issued, which makes every step wait for the loads it
+  // has just sent.  Past the end of the run the last slab is simply requested again.)
+#define MARS_LM_REQUEST(SET)                                                                        \
+  {                                                                                                 \
+    lm_load_global<A_LOADS>(ga[SET], a_tile, a_off, l_kt * kLmBK);                                  \
+    lm_load_global<W_LOADS>(gw[SET], w_tile, w_off, l_kt * kLmBK);                                  \
+    if (++l_kt == KT) {                                                                             \
+      l_kt = 0;                                                                                     \
+      l_tile = min(l_tile + 1, tile_end - 1);                                                       \
+      w_tile = weight + static_cast<size_t>(l_tile) * kLmBN * H;                                    \
+      _Pragma("unroll") for (int i = 0; i < W_LOADS; ++i)                                           \
+        w_off[i] = static_cast<unsigned int>(min(V - 1 - l_tile * kLmBN, srow + i * 32)) * H + schunk; \
+    }                                                                                               \
+  }
+
+#pragma unroll
+  for (int u = 0; u < D; ++u) MARS_LM_REQUEST(u)
+  lm_store_lds<A_LOADS>(ga[0], &sh_a[0][srow][schunk]);
+  lm_store_lds<W_LOADS>(gw[0], &sh_w[0][srow][schunk]);
+  __syncthreads();
+  // operand fragments of the current and the next round (lane l: row l%32 of its block,
+  // elements 8*(l/32) .. +7 of the 16-deep round)
+  u32x4 wf[2][JB], hf[2][IB];
+  lm_load_frags<JB>(wf[0], &sh_w[0][wn * 128 + l32][half * 8]);
+  lm_load_frags<IB>(hf[0], &sh_a[0][wm * WM + l32][half * 8]);
+
+  int step = 0;  // the step being multiplied
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
     f32x16_t acc[JB][IB];
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb)
@@ -109,54 +152,64 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[jb][ib][r] = 0.0f;
 
-    u32x4 ga[A_LOADS], gw[W_LOADS];
-    // (the previous tile ended with a barrier behind its last LDS reads)
-    lm_load_global<A_LOADS>(ga, a_tile, a_off, 0);
-    lm_load_global<W_LOADS>(gw, w_tile, w_off, 0);
-    lm_store_lds<A_LOADS>(ga, &sh_a[0][srow][schunk]);
-    lm_store_lds<W_LOADS>(gw, &sh_w[0][srow][schunk]);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-      const int cur = kt & 1;
-      if (kt + 1 < KT) {  // in flight while this slab is multiplied
-        lm_load_global<A_LOADS>(ga, a_tile, a_off, (kt + 1) * kLmBK);
-        lm_load_global<W_LOADS>(gw, w_tile, w_off, (kt + 1) * kLmBK);
+    for (int kt = 0; kt < KT; kt += D) {
+#pragma unroll
+      for (int u = 0; u < D; ++u, ++step) {
+        const int cur = step & 1;
+        MARS_LM_REQUEST(u)  // set u held this step's operands, which are in LDS by now
+        // Four 16-deep multiplication rounds.  A wave is alone on its SIMD, so nothing hides an
+        // LDS round trip but its own matrix instructions: the fragments of a round are requested
+        // before the twelve MFMAs of the round before it are issued.  The operands of the next
+        // step (set u+1, requested a step ago) go to the other LDS stage in three portions
+        // behind rounds 0..2; the step's only barrier follows them -- by then this stage has
+        // been read for the last time (round 3's fragments are in registers) and the other one
+        // is complete -- so that round 3 can already fetch the next step's first fragments.
+        // The scheduling barriers keep that order.
+        constexpr int kRounds = kLmBK / 16;
+#pragma unroll
+        for (int ks = 0; ks < kRounds; ++ks) {
+          if (ks + 1 < kRounds) {
+            lm_load_frags<JB>(wf[(ks + 1) & 1], &sh_w[cur][wn * 128 + l32][(ks + 1) * 16 + half * 8]);
+            lm_load_frags<IB>(hf[(ks + 1) & 1], &sh_a[cur][wm * WM + l32][(ks + 1) * 16 + half * 8]);
+          } else {
+            lm_load_frags<JB>(wf[0], &sh_w[cur ^ 1][wn * 128 + l32][half * 8]);
+            lm_load_frags<IB>(hf[0], &sh_a[cur ^ 1][wm * WM + l32][half * 8]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+            for (int ib = 0; ib < IB; ++ib)
+              acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[ks & 1][jb]),
+                                                                    __builtin_bit_cast(bf16x8_t, hf[ks & 1][ib]),
+                                                                    acc[jb][ib], 0, 0, 0);
+          if (ks + 1 < kRounds) {  // (after the run's last step this fills a stage nobody uses)
+#pragma unroll
+            for (int i = ks; i < A_LOADS; i += kRounds - 1)
+              *reinterpret_cast<u32x4*>(&sh_a[cur ^ 1][srow + i * 32][schunk]) = ga[(u + 1) % D][i];
+#pragma unroll
+            for (int i = ks; i < W_LOADS; i += kRounds - 1)
+              *reinterpret_cast<u32x4*>(&sh_w[cur ^ 1][srow + i * 32][schunk]) = gw[(u + 1) % D][i];
+          }
+          if (ks + 2 == kRounds) __syncthreads();
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
-#pragma unroll
-      for (int ks = 0; ks < kLmBK / 16; ++ks) {
-        // lane l supplies row l%32 of its block, elements 8*(l/32) .. +7 of the 16-deep step
-        u32x4 wf[JB], hf[IB];
-#pragma unroll
-        for (int jb = 0; jb < JB; ++jb)
-          wf[jb] = *reinterpret_cast<const u32x4*>(&sh_w[cur][wn * 128 + jb * 32 + l32][ks * 16 + half * 8]);
-#pragma unroll
-        for (int ib = 0; ib < IB; ++ib)
-          hf[ib] = *reinterpret_cast<const u32x4*>(&sh_a[cur][wm * WM + ib * 32 + l32][ks * 16 + half * 8]);
-#pragma unroll
-        for (int jb = 0; jb < JB; ++jb)
-#pragma unroll
-          for (int ib = 0; ib < IB; ++ib)
-            acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[jb]),
-                                                                  __builtin_bit_cast(bf16x8_t, hf[ib]), acc[jb][ib], 0, 0, 0);
-      }
-      if (kt + 1 < KT) {
-        lm_store_lds<A_LOADS>(ga, &sh_a[cur ^ 1][srow][schunk]);
-        lm_store_lds<W_LOADS>(gw, &sh_w[cur ^ 1][srow][schunk]);
-      }
-      __syncthreads();
     }
 
-    // The tile's logits, in this lane: hidden-state row m0 + wm*WM + ib*32 + l32, vocabulary entries
-    // n0 + wn*128 + jb*32 + 8*(r/4) + 4*half + r%4.  Round to bf16, take the top-2 of the 16*JB
-    // entries per row block with 32-bit keys (pattern << 16 | 127 - entry: larger value first, then
-    // the lower entry; `half` is the same for all of a lane's entries and is added afterwards).
+    // The tile's logits, in this lane: hidden-state row m0 + wm*WM + ib*32 + l32, vocabulary
+    // entries n0 + wn*128 + jb*32 + 8*(r/4) + 4*half + r%4.  Round to bf16, take the top-2 of the
+    // 16*JB entries per row block with 32-bit keys (pattern << 16 | 127 - entry: larger value
+    // first, then the lower entry; `half` is the same for all of a lane's entries and is added
+    // afterwards).
+    const int n0 = tile * kLmBN;
     const int nbase = n0 + wn * 128 + 4 * half;
     const bool ragged = n0 + kLmBN > V;
 #pragma unroll
     for (int ib = 0; ib < IB; ++ib) {
       uint32_t k1 = 0u, k2 = 0u;
 #pragma unroll
-      for (int jb = 0; jb < JB; ++jb)
+      for (int jb = 0; jb < JB; ++jb) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int e = jb * 32 + 8 * (r / 4) + (r % 4);
@@ -166,12 +219,18 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
           k1 = max(k1, key);
           k2 = max(k2, lo);
         }
-      if (k1 != 0u) top2_insert(best1[ib], best2[ib],
-                                make_key(__uint_as_float(unord16(k1 >> 16) << 16), nbase + 127 - static_cast<int>(k1 & 0x7Fu)));
-      if (k2 != 0u) top2_insert(best1[ib], best2[ib],
-                                make_key(__uint_as_float(unord16(k2 >> 16) << 16), nbase + 127 - static_cast<int>(k2 & 0x7Fu)));
+        // one accumulator block at a time: the operand sets in flight stay in their registers
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (k1 != 0u)
+        top2_insert(best1[ib], best2[ib], make_key(__uint_as_float(unord16(k1 >> 16) << 16),
+                                                   nbase + 127 - static_cast<int>(k1 & 0x7Fu)));
+      if (k2 != 0u)
+        top2_insert(best1[ib], best2[ib], make_key(__uint_as_float(unord16(k2 >> 16) << 16),
+                                                   nbase + 127 - static_cast<int>(k2 & 0x7Fu)));
     }
   }
+#undef MARS_LM_REQUEST
 
   // Lanes l and l + 32 hold the same rows (different vocabulary entries): combine, and the lower
   // half writes the partial result of (row, run, wave column).

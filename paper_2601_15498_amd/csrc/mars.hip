@@ -125,11 +125,15 @@ static ClearArgs clear_args(char* ws, const Layout& L, int B, int N, int K) {
 
 // ---------------------------------------------------------------- LM head fused with the row reduction
 // Slab height: the one that pads the fewest rows (the taller one on a tie: more reuse of the
-// weight tile).  Runs of vocabulary tiles: about one work-group per compute unit in all, so the
-// whole grid is resident at once and every work-group has the same amount of work.
+// weight tile).  Runs of vocabulary tiles: the hardware hands work-group i to die i mod 8, a
+// work-group fills a compute unit, and the slabs of a run share a die (they read the same weight
+// tiles): so at most floor(32 / slabs) runs per die, 8 times that in all, which keeps the whole
+// grid resident at once with the same amount of work for every work-group.  (Two runs too many on
+// one die and its last work-groups start when the others have finished: twice the time.)
 struct LmPlan {
   int bm, slabs, tiles_n, tiles_per_run, runs, parts;
 };
+constexpr int kDies = 8, kUnitsPerDie = kComputeUnits / kDies;
 static LmPlan lm_plan(long rows, int V) {
   LmPlan p;
   long best = -1;
@@ -140,8 +144,9 @@ static LmPlan lm_plan(long rows, int V) {
   }
   p.slabs = static_cast<int>((rows + p.bm - 1) / p.bm);
   p.tiles_n = (V + kLmBN - 1) / kLmBN;
-  int want = kComputeUnits / p.slabs;
-  if (want < 1) want = 1;
+  int per_die = kUnitsPerDie / p.slabs;
+  if (per_die < 1) per_die = 1;
+  int want = kDies * per_die;
   if (want > p.tiles_n) want = p.tiles_n;
   p.tiles_per_run = (p.tiles_n + want - 1) / want;
   p.runs = (p.tiles_n + p.tiles_per_run - 1) / p.tiles_per_run;
@@ -164,7 +169,7 @@ static LmLayout lm_layout(int B, int N, int V, int K) {
 }
 
 static bool lm_sizes_ok(int B, int N, int V, int H, int K) {
-  return sizes_ok(B, N, V, K) && H >= kLmBK && H % kLmBK == 0 && static_cast<long>(B) * N <= (1L << 22);
+  return sizes_ok(B, N, V, K) && H >= kLmBK * kLmDepth && H % (kLmBK * kLmDepth) == 0 && static_cast<long>(B) * N <= (1L << 22);
 }
 
 }  // namespace mars
@@ -429,7 +434,7 @@ int mars_lmhead_verify(const void* hidden, const void* weight, int H, const int3
   Partial* partials = reinterpret_cast<Partial*>(ws + L.partials_off);
   const LmPlan& p = L.plan;
 
-  const dim3 grid(static_cast<unsigned int>(8 * p.slabs * ((p.runs + 7) / 8))), block(kLmThreads);
+  const dim3 grid(static_cast<unsigned int>(kDies * p.slabs * ((p.runs + kDies - 1) / kDies))), block(kLmThreads);
   const bf16_t* hp = static_cast<const bf16_t*>(hidden);
   const bf16_t* wp = static_cast<const bf16_t*>(weight);
 #define MARS_LM_LAUNCH(BM)                                                                                      \
