@@ -74,11 +74,12 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
   __shared__ __attribute__((aligned(16))) bf16_t sh_a[2][BM][kLmStride];
   __shared__ __attribute__((aligned(16))) bf16_t sh_w[2][kLmBN][kLmStride];
 
-  // Work-groups of one run (all slabs) sit on the same die (block index mod 8) next to each
-  // other in launch order: they read the same weight tiles at the same time.
-  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  const int slab = local % slabs, run = (local / slabs) * 8 + xcd;
-  if (run >= runs) return;
+  // (run, slab) pairs are dealt out die by die (block index mod 8 is the die): the slabs of a run
+  // sit next to each other on one die and read the same weight tiles at the same time.
+  const int per_die = gridDim.x >> 3;
+  const int pair = (blockIdx.x & 7) * per_die + (blockIdx.x >> 3);
+  if (pair >= runs * slabs) return;
+  const int run = pair / slabs, slab = pair - run * slabs;
   const int m0 = slab * BM;
   const int tile_begin = run * tiles_per_run, tile_end = min(tiles_n, tile_begin + tiles_per_run);
 

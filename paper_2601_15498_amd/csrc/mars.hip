@@ -125,15 +125,17 @@ static ClearArgs clear_args(char* ws, const Layout& L, int B, int N, int K) {
 
 // ---------------------------------------------------------------- LM head fused with the row reduction
 // Slab height: the one that pads the fewest rows (the taller one on a tie: more reuse of the
-// weight tile).  Runs of vocabulary tiles: the hardware hands work-group i to die i mod 8, a
-// work-group fills a compute unit, and the slabs of a run share a die (they read the same weight
-// tiles): so at most floor(32 / slabs) runs per die, 8 times that in all, which keeps the whole
-// grid resident at once with the same amount of work for every work-group.  (Two runs too many on
-// one die and its last work-groups start when the others have finished: twice the time.)
+// weight tile).  Runs of vocabulary tiles: about one work-group per compute unit in all, so that
+// the whole grid is resident at once with the same amount of work for every work-group.  The
+// hardware hands work-group i to die i mod 8 and a work-group fills a compute unit, so the
+// (run, slab) pairs are dealt out die by die, an equal share to each: the slabs of a run then sit on one die
+// (at most two) and find the weight tiles they share in its L2, and no die is given more
+// work-groups than it has compute units (its last ones would start when the others have
+// finished: twice the time).
 struct LmPlan {
   int bm, slabs, tiles_n, tiles_per_run, runs, parts;
 };
-constexpr int kDies = 8, kUnitsPerDie = kComputeUnits / kDies;
+constexpr int kDies = 8;
 static LmPlan lm_plan(long rows, int V) {
   LmPlan p;
   long best = -1;
@@ -144,9 +146,8 @@ static LmPlan lm_plan(long rows, int V) {
   }
   p.slabs = static_cast<int>((rows + p.bm - 1) / p.bm);
   p.tiles_n = (V + kLmBN - 1) / kLmBN;
-  int per_die = kUnitsPerDie / p.slabs;
-  if (per_die < 1) per_die = 1;
-  int want = kDies * per_die;
+  int want = kComputeUnits / p.slabs;
+  if (want < 1) want = 1;
   if (want > p.tiles_n) want = p.tiles_n;
   p.tiles_per_run = (p.tiles_n + want - 1) / want;
   p.runs = (p.tiles_n + p.tiles_per_run - 1) / p.tiles_per_run;
@@ -434,7 +435,8 @@ int mars_lmhead_verify(const void* hidden, const void* weight, int H, const int3
   Partial* partials = reinterpret_cast<Partial*>(ws + L.partials_off);
   const LmPlan& p = L.plan;
 
-  const dim3 grid(static_cast<unsigned int>(kDies * p.slabs * ((p.runs + kDies - 1) / kDies))), block(kLmThreads);
+  const int pairs = p.runs * p.slabs, per_die = (pairs + kDies - 1) / kDies;
+  const dim3 grid(static_cast<unsigned int>(kDies * per_die)), block(kLmThreads);
   const bf16_t* hp = static_cast<const bf16_t*>(hidden);
   const bf16_t* wp = static_cast<const bf16_t*>(weight);
 #define MARS_LM_LAUNCH(BM)                                                                                      \
