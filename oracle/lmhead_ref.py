@@ -80,33 +80,42 @@ def lmhead_verify(hidden_bits, weight_bits, draft_tokens, tree_parent, theta, in
     return out
 
 
-def screen_lmhead(w, clearance=4e-5, guard=1e-4, indicator=mars_ref.IND_LOGIT_RATIO, max_rounds=50):
+def screen_lmhead(w, clearance=4e-5, guard=1e-4, indicator=mars_ref.IND_LOGIT_RATIO, max_rounds=50, requests=None):
     """Redraw (``w.redraw_rows``) the rows of an LM-head workload whose deciding logits lie within
     ``clearance`` (relative) of a bf16 rounding boundary, or whose low-margin quantity lies within
     ``guard`` of the request's threshold, until none is left.  Returns ``lmhead_verify``'s result
     for the final inputs.  Only the redrawn rows and the two vocabulary columns each of them owns
-    are recomputed between rounds."""
+    are recomputed between rounds.
+
+    ``requests`` (a list of request indices) restricts the work to those requests: the result then
+    describes the sub-batch they form, in the order given (a redrawn row still changes the weight
+    rows it owns, which every request sees)."""
     B, N, H, V = w.B, w.N, w.H, w.V
+    req = np.arange(B) if requests is None else np.asarray(requests, dtype=np.int64)
+    flat = (req[:, None] * N + np.arange(N)[None, :]).reshape(-1)        # flat rows of the sub-batch
+    theta = np.asarray(w.theta, np.float32)[req]
     exact = None
     for round_ in range(1, max_rounds + 1):
-        out = lmhead_verify(w.hidden, w.weight, w.draft_tokens, w.tree_parent, w.theta, indicator, exact)
+        hid = w.hidden.reshape(B * N, H)
+        out = lmhead_verify(hid[flat].reshape(req.size, N, H), w.weight, w.draft_tokens[req], w.tree_parent[req],
+                            theta, indicator, exact)
         exact = out["exact"]
         st = out["stats"]
-        th = np.asarray(w.theta, np.float64)[:, None]
+        th = theta.astype(np.float64)[:, None]
         if indicator == mars_ref.IND_LOGIT_RATIO:
             near = (st["z1"] > 0) & (np.abs(st["ratio"] - th) < guard)
         elif indicator == mars_ref.IND_PROB_RATIO:
             near = np.abs(st["prob_ratio"] - th) < guard
         else:
             near = np.abs(st["gap"] - th) < guard
-        dirty = np.nonzero(((out["clearance"] < clearance) | near).reshape(-1))[0]
+        dirty = np.nonzero(((out["clearance"] < clearance) | near).reshape(-1))[0]   # positions in the sub-batch
         if dirty.size == 0:
             return out
-        w.redraw_rows(dirty, round_)
+        w.redraw_rows(flat[dirty], round_)
         hid = w.hidden.reshape(B * N, H)
-        exact[dirty] = logits_exact(hid[dirty], w.weight)
-        cols = w.planted.reshape(B * N, 2)[dirty].reshape(-1)
+        exact[dirty] = logits_exact(hid[flat[dirty]], w.weight)
+        cols = w.planted.reshape(B * N, 2)[flat[dirty]].reshape(-1)
         cols = cols[cols >= 0]
         if cols.size:
-            exact[:, cols] = logits_exact(hid, w.weight[cols])
+            exact[:, cols] = logits_exact(hid[flat], w.weight[cols])
     raise RuntimeError("rows still inside a guard band after the last round")

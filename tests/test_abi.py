@@ -27,7 +27,8 @@ def declared_functions():
 
 
 def test_header_declares_the_expected_entry_points():
-    assert declared_functions() == ["mars_margin_stats", "mars_row_reduce", "mars_row_stats", "mars_status_string",
+    assert declared_functions() == ["mars_lmhead_verify", "mars_lmhead_workspace_bytes", "mars_margin_stats",
+                                    "mars_row_reduce", "mars_row_stats", "mars_status_string",
                                     "mars_verify", "mars_verify_ex", "mars_version", "mars_workspace_bytes",
                                     "mars_workspace_bytes_ex"]
 
@@ -135,6 +136,37 @@ def test_host_side_argument_errors_enqueue_nothing(lib):
     assert rs(null, 0, p, ctypes.c_float(0.0), 1, 1, 10, p, p, ctypes.c_size_t(1 << 20), null) == -1
     assert rs(p, 3, p, ctypes.c_float(0.0), 1, 1, 10, p, p, ctypes.c_size_t(1 << 20), null) == -2
     assert rs(p, 0, p, ctypes.c_float(0.0), 1, 1, 10, p, p, ctypes.c_size_t(8), null) == -3
+
+
+def test_lmhead_argument_errors_enqueue_nothing(lib):
+    from paper_2601_15498_amd.binding import VerifyOptionsStruct
+    p = ctypes.c_void_p(0x1000)  # never dereferenced
+    null = ctypes.c_void_p(0)
+    wsb = lib.mars_lmhead_workspace_bytes
+    assert wsb(16, 60, 151936, 4096, 1) > 0 and wsb(16, 60, 151936, 4096, 1) % 256 == 0
+    assert wsb(16, 60, 151936, 4096, 0) == wsb(16, 60, 151936, 4096, 1) < wsb(16, 60, 151936, 4096, 7)
+    for B, N, V, H, K in ((0, 4, 100, 128, 1), (1, 0, 100, 128, 1), (1, 1025, 100, 128, 1), (1, 4, 1, 128, 1),
+                          (1, 4, 100, 0, 1), (1, 4, 100, 64, 1), (1, 4, 100, 200, 1), (1, 4, 100, 128, 65)):
+        assert wsb(B, N, V, H, K) == 0, (B, N, V, H, K)
+    ok = dict(h=p, w=p, H=256, tok=p, par=p, theta=p, B=2, N=4, V=100, mask=p, alen=p, path=p, bonus=p,
+              ws=p, wsb=1 << 22, opt=None)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return lib.mars_lmhead_verify(a["h"], a["w"], a["H"], a["tok"], a["par"], a["theta"], a["B"], a["N"], a["V"],
+                                      a["mask"], a["alen"], a["path"], a["bonus"], null, null, null, a["ws"],
+                                      ctypes.c_size_t(a["wsb"]), null, ctypes.byref(a["opt"]) if a["opt"] else None)
+
+    for key in ("h", "w", "tok", "par", "theta", "mask", "alen", "path", "bonus"):
+        assert call(**{key: null}) == -1, key
+    assert call(h=ctypes.c_void_p(0x1008)) == -1 and call(w=ctypes.c_void_p(0x1004)) == -1   # 16-byte alignment
+    assert call(H=0) == -1 and call(H=192) == -1 and call(H=-128) == -1                         # multiple of 128
+    assert call(B=0) == -1 and call(N=1025) == -1 and call(V=1) == -1
+    assert call(ws=null) == -3 and call(wsb=64) == -3 and call(ws=ctypes.c_void_p(0x1010)) == -3
+    assert call(opt=VerifyOptionsStruct(5, 1, 0, 0, None, None, None, None)) == -1              # unknown indicator
+    assert call(opt=VerifyOptionsStruct(0, 65, 0, 0, None, None, None, None)) == -1
+    assert call(opt=VerifyOptionsStruct(0, 1, 0, 1, None, None, None, None)) == -1              # the two parts cannot be split here
+    assert call(opt=VerifyOptionsStruct(0, 1, 0, 0, 0x1000, None, None, None)) == -1            # commit outputs: all or none
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
