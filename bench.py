@@ -14,6 +14,9 @@ input sets are rotated so that a step never finds its logits in the 256 MB memor
   sweep7    the same with seven thresholds per request (0.84 .. 0.96) from one read of the logits
   margin    mars_margin_stats on the same logits (top-2 statistics per row and their histograms)
   spd       mars_verify on chains of 6 drafts with a dense draft distribution, B = 128, T = 1
+  lmhead    mars_lmhead_verify: greedy verification from the last hidden states (H = 4096) and the
+            LM-head weight [151 936, 4096], the logits never written to memory; its roofline object
+            is the matrix-core one (bf16 MFMA peak) of the fused kernel
 
 The timed steps are issued round-robin on ``--streams`` HIP streams (default 2), each with its own
 workspace and outputs: the library keeps no state and calls with different workspaces may overlap,
@@ -38,6 +41,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
 N_BUFFERS = 4
 PARTIAL_BYTES = 24     # one partial result per (row, split, wave) written by the row reduction
 WAVES_PER_GROUP = 8    # waves per work-group of the row reduction
@@ -55,6 +59,9 @@ WORKLOADS = {
                                "of z1, z2/z1, p2/p1 (40/50/50 cells)"),
     "spd": dict(cfg=5, what="chains of 6 drafts (N=7), B=128, V=151936, bf16 logits, dense fp32 draft distribution, "
                             "T=1, theta=0.9"),
+    "lmhead": dict(cfg=None, what="greedy verification from hidden states: B=16, 60-node tree per request, H=4096, "
+                                  "V=151936, bf16 hidden states and LM-head weight, theta=0.9; logits formed, reduced "
+                                  "and dropped inside one kernel"),
 }
 
 
@@ -93,6 +100,94 @@ def measured_pass_traffic():
     return k1 + t["tail_hbm_bytes_per_launch"]
 
 
+def main_lmhead(args) -> int:
+    """--workload lmhead: one step = one mars_lmhead_verify call (LM head + top-2 + Alg. 1)."""
+    import numpy as np
+    import torch
+
+    from mars_inputs.lmhead import LMHEAD_CONFIGS, make_lmhead_workload
+    from paper_2601_15498_amd import binding as M
+
+    if not torch.cuda.is_available():
+        print("bench.py needs the GPU", file=sys.stderr)
+        return 2
+    M.lib()
+    dev = torch.device("cuda:0")
+    spec = dict(LMHEAD_CONFIGS["headline"])
+    name = spec.pop("name")
+    t_gen = time.perf_counter()
+    w = make_lmhead_workload(name, seed=2, **spec)
+    t_gen = time.perf_counter() - t_gen
+    B, N, H, V = w.B, w.N, w.H, w.V
+    rows = B * N
+    d = dict(h=torch.from_numpy(w.hidden).to(dev), w=torch.from_numpy(w.weight).to(dev),
+             tok=torch.from_numpy(w.draft_tokens).to(dev), par=torch.from_numpy(w.tree_parent).to(dev),
+             th=torch.from_numpy(np.ascontiguousarray(w.theta, np.float32)).to(dev))
+    out = M.VerifyOutputs(B, N, dev, want_diag=False)
+    ws = torch.empty(M.mars_lmhead_workspace_bytes(B, N, V, H), dtype=torch.uint8, device=dev)
+
+    def step(stages=0):
+        M.mars_lmhead_verify(d["h"], d["w"], d["tok"], d["par"], d["th"], out, ws, stages=stages)
+
+    def timed(n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            step()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    timed(args.warmup)
+    elapsed = timed(args.steps)
+    tau = float(out.accept_len.float().mean().item() + 1.0)
+    statuses = int((out.request_status != 0).sum().item())
+    # the fused LM-head kernel by itself: HIP events on the stream it is launched on
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(min(args.warmup, 10)):
+        step(M.MARS_STAGE_ROWS)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        step(M.MARS_STAGE_ROWS)
+    e1.record()
+    torch.cuda.synchronize()
+    k_ms = e0.elapsed_time(e1) / args.steps
+    flops = 2.0 * rows * H * V
+    achieved = flops / (k_ms * 1e-3) / 1e12
+    result = {
+        "metric": "rows/s + achieved bf16 MFMA TFLOP/s vs peak, workload 'lmhead'",
+        "value": rows * args.steps / elapsed, "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": WORKLOADS["lmhead"]["what"], "B": B, "N": N, "H": H, "V": V, "rows_per_step": rows,
+                   "streams": 1, "mean_tau": tau, "requests_with_nonzero_status": statuses,
+                   "weight_bytes": V * H * 2, "weight_stream_GBps": V * H * 2 / (k_ms * 1e-3) / 1e9,
+                   "input_generation_s": round(t_gen, 1)},
+        "roofline": {"bound": "mfma", "kernel": "lmhead_reduce_kernel<192>", "achieved": achieved,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": None, "algorithmic_flops_per_launch": flops, "avg_launch_us": k_ms * 1e3},
+    }
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_info
+
+        from oracle import lmhead_ref
+        sample = 2  # requests
+        reps, cpu_s = 0, 0.0
+        while reps < 2 or (cpu_s < 10.0 and reps < 20):
+            t = time.perf_counter()
+            lmhead_ref.lmhead_verify(w.hidden[:sample], w.weight, w.draft_tokens[:sample], w.tree_parent[:sample],
+                                     w.theta[:sample])
+            cpu_s += time.perf_counter() - t
+            reps += 1
+        threads = max([int(i.get("num_threads", 1)) for i in threadpool_info()] or [1])
+        result["cpu_baseline"] = {"value": sample * N * reps / cpu_s, "unit": "rows/s", "cores": threads, "kind": "oracle",
+                                  "sample": f"the first {sample} requests ({sample * N} rows against the whole weight), "
+                                            f"{reps} passes, {cpu_s:.1f} s wall; fp64 matrix product by the BLAS numpy "
+                                            "links, then the C oracle"}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -109,6 +204,9 @@ def main() -> int:
         print("bench.py measures one GPU only: the verification pass is per request and needs no "
               "exchange between GPUs; run it with --gpus 1", file=sys.stderr)
         return 2
+
+    if args.workload == "lmhead":
+        return main_lmhead(args)
 
     import numpy as np
     import torch

@@ -330,8 +330,9 @@ int mars_margin_stats(const void* logits, int logits_dtype, const float* theta, 
  *   theta, draft_tokens, tree_parent, outputs, options: as for mars_verify_ex with temperature 0
  *            (request_status, decision, stats optional; options may be NULL).
  *   workspace device, 256-byte aligned, >= mars_lmhead_workspace_bytes(B,N,V,H,n_theta).
- * Returns MARS_OK or a negative code; MARS_ERR_ARG also for H not a multiple of 128, misaligned
- * hidden / weight, or options->stages naming only one of the two parts.  On MARS_ERR_HIP kernels launched before the failing one stay enqueued;
+ *            options->stages works as for mars_verify_ex: MARS_STAGE_ROWS is the fused LM-head kernel.
+ * Returns MARS_OK or a negative code; MARS_ERR_ARG also for H not a multiple of 128 or misaligned
+ * hidden / weight.  On MARS_ERR_HIP kernels launched before the failing one stay enqueued;
  * otherwise an error enqueues nothing.  Calls with workspaces of their own may overlap.
  */
 size_t mars_lmhead_workspace_bytes(int B, int N, int V, int H, int n_theta);

@@ -292,7 +292,7 @@ def mars_lmhead_workspace_bytes(B: int, N: int, V: int, H: int, n_theta: int = 1
 def mars_lmhead_verify(hidden: torch.Tensor, weight: torch.Tensor, draft_tokens: torch.Tensor,
                        tree_parent: torch.Tensor, theta: torch.Tensor, out: VerifyOutputs = None,
                        workspace: torch.Tensor = None, indicator: int = MARS_IND_LOGIT_RATIO, n_theta: int = 1,
-                       want_commit: bool = False) -> VerifyOutputs:
+                       want_commit: bool = False, stages: int = 0) -> VerifyOutputs:
     """Greedy verification from the last hidden states [B,N,H] and the LM-head weight [V,H] (both bf16, or
     their bit patterns): the logits are formed, reduced and dropped inside one kernel.  See include/mars.h."""
     B, N, H = hidden.shape
@@ -311,7 +311,7 @@ def mars_lmhead_verify(hidden: torch.Tensor, weight: torch.Tensor, draft_tokens:
         if n == 0:
             raise MarsError(f"sizes out of range: B={B} N={N} V={V} H={H} n_theta={n_theta}")
         workspace = torch.empty(n, dtype=torch.uint8, device=dev)
-    opt = VerifyOptionsStruct(int(indicator), int(n_theta), 0, 0,
+    opt = VerifyOptionsStruct(int(indicator), int(n_theta), 0, int(stages),
                               None if out.out_tokens is None else out.out_tokens.data_ptr(),
                               None if out.out_len is None else out.out_len.data_ptr(),
                               None if out.keep_rows is None else out.keep_rows.data_ptr(),

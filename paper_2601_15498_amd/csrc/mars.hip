@@ -411,13 +411,13 @@ int mars_lmhead_verify(const void* hidden, const void* weight, int H, const int3
     return MARS_ERR_ARG;
   if (reinterpret_cast<uintptr_t>(hidden) % 16 != 0 || reinterpret_cast<uintptr_t>(weight) % 16 != 0)
     return MARS_ERR_ARG;
-  int K = 1, indicator = MARS_IND_LOGIT_RATIO;
+  int K = 1, indicator = MARS_IND_LOGIT_RATIO, lm_stages = MARS_STAGE_ROWS | MARS_STAGE_REQUESTS;
   int32_t *out_tokens = nullptr, *out_len = nullptr, *keep_rows = nullptr, *keep_offsets = nullptr;
   if (options) {
     K = options->n_theta == 0 ? 1 : options->n_theta;
     indicator = options->indicator;
     if (options->spin_limit < 0 || options->stages < 0 || options->stages > 3) return MARS_ERR_ARG;
-    if (options->stages != 0 && options->stages != (MARS_STAGE_ROWS | MARS_STAGE_REQUESTS)) return MARS_ERR_ARG;
+    if (options->stages != 0) lm_stages = options->stages;
     out_tokens = options->out_tokens; out_len = options->out_len;
     keep_rows = options->keep_rows; keep_offsets = options->keep_offsets;
   }
@@ -442,13 +442,16 @@ int mars_lmhead_verify(const void* hidden, const void* weight, int H, const int3
 #define MARS_LM_LAUNCH(BM)                                                                                      \
   hipLaunchKernelGGL((lmhead_reduce_kernel<BM>), grid, block, 0, stream, hp, wp, rows, V, H, p.slabs, p.tiles_n, \
                      p.tiles_per_run, p.runs, partials)
-  switch (p.bm) {
-    case 64: MARS_LM_LAUNCH(64); break;
-    case 128: MARS_LM_LAUNCH(128); break;
-    default: MARS_LM_LAUNCH(192); break;
+  if (lm_stages & MARS_STAGE_ROWS) {
+    switch (p.bm) {
+      case 64: MARS_LM_LAUNCH(64); break;
+      case 128: MARS_LM_LAUNCH(128); break;
+      default: MARS_LM_LAUNCH(192); break;
+    }
+    if (hipGetLastError() != hipSuccess) return MARS_ERR_HIP;
   }
 #undef MARS_LM_LAUNCH
-  if (hipGetLastError() != hipSuccess) return MARS_ERR_HIP;
+  if (!(lm_stages & MARS_STAGE_REQUESTS)) return MARS_OK;
 
   TailArgs a;
   a.logits = nullptr; a.tok = draft_tokens; a.par = tree_parent; a.dprobs = nullptr;

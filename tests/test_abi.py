@@ -165,7 +165,7 @@ def test_lmhead_argument_errors_enqueue_nothing(lib):
     assert call(ws=null) == -3 and call(wsb=64) == -3 and call(ws=ctypes.c_void_p(0x1010)) == -3
     assert call(opt=VerifyOptionsStruct(5, 1, 0, 0, None, None, None, None)) == -1              # unknown indicator
     assert call(opt=VerifyOptionsStruct(0, 65, 0, 0, None, None, None, None)) == -1
-    assert call(opt=VerifyOptionsStruct(0, 1, 0, 1, None, None, None, None)) == -1              # the two parts cannot be split here
+    assert call(opt=VerifyOptionsStruct(0, 1, 0, 4, None, None, None, None)) == -1              # unknown stages
     assert call(opt=VerifyOptionsStruct(0, 1, 0, 0, 0x1000, None, None, None)) == -1            # commit outputs: all or none
 
 
