@@ -100,6 +100,19 @@ def measured_pass_traffic():
     return k1 + t["tail_hbm_bytes_per_launch"]
 
 
+def measured_lmhead_traffic():
+    """Bytes the fused LM-head kernel moves between L2 and the memory side per launch on its benchmark
+    workload, from the committed counter runs; None once the kernel source has changed since."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "lmhead_reduce_traffic.json")) as fh:
+            t = json.load(fh)
+    except (OSError, ValueError):
+        return None
+    if t.get("kernel_source_digest") != kernel_source_digest(("common.h", "lmhead.h")):
+        return None
+    return t.get("hbm_bytes_per_launch")
+
+
 def main_lmhead(args) -> int:
     """--workload lmhead: one step = one mars_lmhead_verify call (LM head + top-2 + Alg. 1)."""
     import numpy as np
@@ -165,7 +178,8 @@ def main_lmhead(args) -> int:
                    "input_generation_s": round(t_gen, 1)},
         "roofline": {"bound": "mfma", "kernel": "lmhead_reduce_kernel<192>", "achieved": achieved,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": None, "algorithmic_flops_per_launch": flops, "avg_launch_us": k_ms * 1e3},
+                     "traffic": measured_lmhead_traffic(), "algorithmic_flops_per_launch": flops,
+                     "algorithmic_bytes_per_launch": V * H * 2 + rows * H * 2, "avg_launch_us": k_ms * 1e3},
     }
     if not args.no_cpu_baseline:
         from threadpoolctl import threadpool_info

@@ -29,14 +29,15 @@ constexpr int kLmChunks = kLmBK / 8;      // 16-byte chunks per staged row
 constexpr int kLmDepth = 2;               // steps between the request of an operand slab and its use
 constexpr int kLmMaxBM = 192;             // tallest slab of hidden-state rows (256 no longer fits the register file)
 
-// Order-preserving 16-bit pattern of a bf16 value (larger value = larger pattern).
-__device__ __forceinline__ uint32_t ord16(uint32_t u) { return (u & 0x8000u) ? (~u & 0xFFFFu) : (u | 0x8000u); }
-__device__ __forceinline__ uint32_t unord16(uint32_t o) { return (o & 0x8000u) ? (o & 0x7FFFu) : (~o & 0xFFFFu); }
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
-// fp32 -> bf16, round to nearest even (finite inputs), as a 16-bit pattern.
-__device__ __forceinline__ uint32_t bf16_rne(float x) {
-  const uint32_t u = __float_as_uint(x + 0.0f);
-  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+// The bits of a float as a signed integer with the same order (an involution: negative values
+// have their magnitude bits flipped).
+__device__ __forceinline__ int lm_ordered(int t) { return t ^ static_cast<int>(static_cast<uint32_t>(t >> 31) >> 1); }
+// The bf16 value in the upper half of a key, widened.
+__device__ __forceinline__ float lm_key_value(int key) {
+  return __int_as_float(static_cast<int>(static_cast<uint32_t>(lm_ordered(key & static_cast<int>(0xFFFF0000u))) & 0xFFFF0000u));
 }
 
 // Staging of one operand slab: n 16-byte chunks per thread, rows 32 apart.
@@ -199,36 +200,43 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
     }
 
     // The tile's logits, in this lane: hidden-state row m0 + wm*WM + ib*32 + l32, vocabulary
-    // entries n0 + wn*128 + jb*32 + 8*(r/4) + 4*half + r%4.  Round to bf16, take the top-2 of the
-    // 16*JB entries per row block with 32-bit keys (pattern << 16 | 127 - entry: larger value
-    // first, then the lower entry; `half` is the same for all of a lane's entries and is added
-    // afterwards).
+    // entries n0 + wn*128 + jb*32 + 8*(r/4) + 4*half + r%4.  Round to bf16 (two at a time, the
+    // hardware conversion: nearest even), take the top-2 of the 16*JB entries per row block with
+    // signed 32-bit keys: the bf16 pattern made order-preserving in the upper half, 127 - entry
+    // below it (larger value first, then the lower entry; `half` is the same for all of a
+    // lane's entries and is added afterwards).  INT_MIN = no candidate.
     const int n0 = tile * kLmBN;
     const int nbase = n0 + wn * 128 + 4 * half;
     const bool ragged = n0 + kLmBN > V;
+    constexpr int kNone = -2147483647 - 1;
 #pragma unroll
     for (int ib = 0; ib < IB; ++ib) {
-      uint32_t k1 = 0u, k2 = 0u;
+      int k1 = kNone, k2 = kNone;
 #pragma unroll
       for (int jb = 0; jb < JB; ++jb) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int e = jb * 32 + 8 * (r / 4) + (r % 4);
-          uint32_t key = (ord16(bf16_rne(acc[jb][ib][r])) << 16) | static_cast<uint32_t>(127 - e);
-          if (ragged && nbase + e >= V) key = 0u;
-          const uint32_t lo = min(k1, key);
-          k1 = max(k1, key);
-          k2 = max(k2, lo);
+        for (int r = 0; r < 16; r += 2) {
+          const f32x2_t pair = {acc[jb][ib][r], acc[jb][ib][r + 1]};
+          const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, bf16x2_t));
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const int e = jb * 32 + 8 * (r / 4) + (r % 4) + h;
+            // widened again; + 0 turns -0 into +0, so that equal values have equal keys
+            const int t = __float_as_int(__uint_as_float(h ? (w & 0xFFFF0000u) : (w << 16)) + 0.0f);
+            int key = static_cast<int>((static_cast<uint32_t>(lm_ordered(t)) & 0xFFFF0000u) | static_cast<uint32_t>(127 - e));
+            if (ragged && nbase + e >= V) key = kNone;
+            const int lo = min(k1, key);
+            k1 = max(k1, key);
+            k2 = max(k2, lo);
+          }
         }
         // one accumulator block at a time: the operand sets in flight stay in their registers
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (k1 != 0u)
-        top2_insert(best1[ib], best2[ib], make_key(__uint_as_float(unord16(k1 >> 16) << 16),
-                                                   nbase + 127 - static_cast<int>(k1 & 0x7Fu)));
-      if (k2 != 0u)
-        top2_insert(best1[ib], best2[ib], make_key(__uint_as_float(unord16(k2 >> 16) << 16),
-                                                   nbase + 127 - static_cast<int>(k2 & 0x7Fu)));
+      if (k1 != kNone)
+        top2_insert(best1[ib], best2[ib], make_key(lm_key_value(k1), nbase + 127 - (k1 & 0x7F)));
+      if (k2 != kNone)
+        top2_insert(best1[ib], best2[ib], make_key(lm_key_value(k2), nbase + 127 - (k2 & 0x7F)));
     }
   }
 #undef MARS_LM_REQUEST
