@@ -119,22 +119,28 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
 
   // (Unconditional on purpose: with a request under a branch the compiler has to place its
   // s_waitcnt for the case that nothing was issued, which makes every step wait for the loads it
-  // has just sent.  Past the end of the run the last slab is simply requested again.)
+  // has just sent.  Past the end of the run the last slab is simply requested again.  The
+  // bookkeeping with its branch is kept apart, so that the loads share a scheduling region with
+  // the matrix instructions they are interleaved with.)
 #define MARS_LM_REQUEST(SET)                                                                        \
   {                                                                                                 \
     lm_load_global<A_LOADS>(ga[SET], a_tile, a_off, l_kt * kLmBK);                                  \
     lm_load_global<W_LOADS>(gw[SET], w_tile, w_off, l_kt * kLmBK);                                  \
-    if (++l_kt == KT) {                                                                             \
-      l_kt = 0;                                                                                     \
-      l_tile = min(l_tile + 1, tile_end - 1);                                                       \
-      w_tile = weight + static_cast<size_t>(l_tile) * kLmBN * H;                                    \
-      _Pragma("unroll") for (int i = 0; i < W_LOADS; ++i)                                           \
-        w_off[i] = static_cast<unsigned int>(min(V - 1 - l_tile * kLmBN, srow + i * 32)) * H + schunk; \
-    }                                                                                               \
+  }
+#define MARS_LM_ADVANCE()                                                                           \
+  if (++l_kt == KT) {                                                                               \
+    l_kt = 0;                                                                                       \
+    l_tile = min(l_tile + 1, tile_end - 1);                                                         \
+    w_tile = weight + static_cast<size_t>(l_tile) * kLmBN * H;                                      \
+    _Pragma("unroll") for (int i = 0; i < W_LOADS; ++i)                                             \
+      w_off[i] = static_cast<unsigned int>(min(V - 1 - l_tile * kLmBN, srow + i * 32)) * H + schunk; \
   }
 
 #pragma unroll
-  for (int u = 0; u < D; ++u) MARS_LM_REQUEST(u)
+  for (int u = 0; u < D; ++u) {
+    MARS_LM_REQUEST(u)
+    MARS_LM_ADVANCE()
+  }
   lm_store_lds<A_LOADS>(ga[0], &sh_a[0][srow][schunk]);
   lm_store_lds<W_LOADS>(gw[0], &sh_w[0][srow][schunk]);
   __syncthreads();
@@ -158,26 +164,23 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
 #pragma unroll
       for (int u = 0; u < D; ++u, ++step) {
         const int cur = step & 1;
-        MARS_LM_REQUEST(u)  // set u held this step's operands, which are in LDS by now
-        // Four 16-deep multiplication rounds.  A wave is alone on its SIMD, so nothing hides an
-        // LDS round trip but its own matrix instructions: the fragments of a round are requested
-        // before the twelve MFMAs of the round before it are issued.  The operands of the next
-        // step (set u+1, requested a step ago) go to the other LDS stage in three portions
-        // behind rounds 0..2; the step's only barrier follows them -- by then this stage has
-        // been read for the last time (round 3's fragments are in registers) and the other one
-        // is complete -- so that round 3 can already fetch the next step's first fragments.
-        // The scheduling barriers keep that order.
+        // Four 16-deep multiplication rounds of twelve MFMAs.  A wave is alone on its SIMD, so
+        // nothing hides a memory instruction's issue time or an LDS round trip but its own matrix
+        // instructions: every memory instruction of the step is slotted between two MFMAs
+        // (sched_group_barrier pins that order).  Rounds 0..2: the fragments of the next round
+        // (7 LDS reads), the step's operand request for two steps ahead (set u held this step's
+        // operands, which are in LDS by now: 14 global loads) and the operands of the next step
+        // (set u+1, requested a step ago: 14 LDS writes into the other stage).  The step's only
+        // barrier follows round 2 -- by then this stage has been read for the last time (round
+        // 3's fragments are in registers) and the other one is complete -- so that round 3 can
+        // already fetch the next step's first fragments.
         constexpr int kRounds = kLmBK / 16;
+        const bf16_t* __restrict__ a_src = a_tile + l_kt * kLmBK;
+        const bf16_t* __restrict__ w_src = w_tile + l_kt * kLmBK;
 #pragma unroll
-        for (int ks = 0; ks < kRounds; ++ks) {
-          if (ks + 1 < kRounds) {
-            lm_load_frags<JB>(wf[(ks + 1) & 1], &sh_w[cur][wn * 128 + l32][(ks + 1) * 16 + half * 8]);
-            lm_load_frags<IB>(hf[(ks + 1) & 1], &sh_a[cur][wm * WM + l32][(ks + 1) * 16 + half * 8]);
-          } else {
-            lm_load_frags<JB>(wf[0], &sh_w[cur ^ 1][wn * 128 + l32][half * 8]);
-            lm_load_frags<IB>(hf[0], &sh_a[cur ^ 1][wm * WM + l32][half * 8]);
-          }
-          __builtin_amdgcn_sched_barrier(0);
+        for (int ks = 0; ks + 1 < kRounds; ++ks) {
+          lm_load_frags<JB>(wf[(ks + 1) & 1], &sh_w[cur][wn * 128 + l32][(ks + 1) * 16 + half * 8]);
+          lm_load_frags<IB>(hf[(ks + 1) & 1], &sh_a[cur][wm * WM + l32][(ks + 1) * 16 + half * 8]);
 #pragma unroll
           for (int jb = 0; jb < JB; ++jb)
 #pragma unroll
@@ -185,17 +188,51 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
               acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[ks & 1][jb]),
                                                                     __builtin_bit_cast(bf16x8_t, hf[ks & 1][ib]),
                                                                     acc[jb][ib], 0, 0, 0);
-          if (ks + 1 < kRounds) {  // (after the run's last step this fills a stage nobody uses)
+          // this round's share of the request (set u) and of the LDS writes (set u+1; after the
+          // run's last step they fill a stage nobody uses)
+          int moves = 0;
 #pragma unroll
-            for (int i = ks; i < A_LOADS; i += kRounds - 1)
-              *reinterpret_cast<u32x4*>(&sh_a[cur ^ 1][srow + i * 32][schunk]) = ga[(u + 1) % D][i];
-#pragma unroll
-            for (int i = ks; i < W_LOADS; i += kRounds - 1)
-              *reinterpret_cast<u32x4*>(&sh_w[cur ^ 1][srow + i * 32][schunk]) = gw[(u + 1) % D][i];
+          for (int i = ks; i < A_LOADS; i += kRounds - 1, ++moves) {
+            ga[u][i] = *reinterpret_cast<const u32x4*>(a_src + a_off[i]);
+            *reinterpret_cast<u32x4*>(&sh_a[cur ^ 1][srow + i * 32][schunk]) = ga[(u + 1) % D][i];
           }
-          if (ks + 2 == kRounds) __syncthreads();
+#pragma unroll
+          for (int i = ks; i < W_LOADS; i += kRounds - 1, ++moves) {
+            gw[u][i] = *reinterpret_cast<const u32x4*>(w_src + w_off[i]);
+            *reinterpret_cast<u32x4*>(&sh_w[cur ^ 1][srow + i * 32][schunk]) = gw[(u + 1) % D][i];
+          }
+          // the order inside the round: an MFMA, then at most one instruction of each kind
+          constexpr int kMfma = JB * IB;
+          constexpr int kMoves = (A_LOADS + kRounds - 2) / (kRounds - 1) + (W_LOADS + kRounds - 2) / (kRounds - 1);
+#pragma unroll
+          for (int i = 0; i < kMfma; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  // one MFMA
+            if (i < JB + IB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                 // one LDS read
+            if ((i * kMoves) / kMfma != ((i + 1) * kMoves) / kMfma) {
+              __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                // one global load
+              __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                                // one LDS write
+            }
+          }
+          (void)moves;
           __builtin_amdgcn_sched_barrier(0);
         }
+        __syncthreads();
+        lm_load_frags<JB>(wf[0], &sh_w[cur ^ 1][wn * 128 + l32][half * 8]);
+        lm_load_frags<IB>(hf[0], &sh_a[cur ^ 1][wm * WM + l32][half * 8]);
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+          for (int ib = 0; ib < IB; ++ib)
+            acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[(kRounds - 1) & 1][jb]),
+                                                                  __builtin_bit_cast(bf16x8_t, hf[(kRounds - 1) & 1][ib]),
+                                                                  acc[jb][ib], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < JB * IB; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (i < JB + IB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        MARS_LM_ADVANCE()
       }
     }
 
@@ -240,6 +277,7 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
     }
   }
 #undef MARS_LM_REQUEST
+#undef MARS_LM_ADVANCE
 
   // Lanes l and l + 32 hold the same rows (different vocabulary entries): combine, and the lower
   // half writes the partial result of (row, run, wave column).
