@@ -175,63 +175,54 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
         // 3's fragments are in registers) and the other one is complete -- so that round 3 can
         // already fetch the next step's first fragments.
         constexpr int kRounds = kLmBK / 16;
+        constexpr int kMfma = JB * IB;  // MFMAs per round
         const bf16_t* __restrict__ a_src = a_tile + l_kt * kLmBK;
         const bf16_t* __restrict__ w_src = w_tile + l_kt * kLmBK;
 #pragma unroll
-        for (int ks = 0; ks + 1 < kRounds; ++ks) {
-          lm_load_frags<JB>(wf[(ks + 1) & 1], &sh_w[cur][wn * 128 + l32][(ks + 1) * 16 + half * 8]);
-          lm_load_frags<IB>(hf[(ks + 1) & 1], &sh_a[cur][wm * WM + l32][(ks + 1) * 16 + half * 8]);
-#pragma unroll
-          for (int jb = 0; jb < JB; ++jb)
-#pragma unroll
-            for (int ib = 0; ib < IB; ++ib)
-              acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[ks & 1][jb]),
-                                                                    __builtin_bit_cast(bf16x8_t, hf[ks & 1][ib]),
-                                                                    acc[jb][ib], 0, 0, 0);
-          // this round's share of the request (set u) and of the LDS writes (set u+1; after the
-          // run's last step they fill a stage nobody uses)
-          int moves = 0;
-#pragma unroll
-          for (int i = ks; i < A_LOADS; i += kRounds - 1, ++moves) {
-            ga[u][i] = *reinterpret_cast<const u32x4*>(a_src + a_off[i]);
-            *reinterpret_cast<u32x4*>(&sh_a[cur ^ 1][srow + i * 32][schunk]) = ga[(u + 1) % D][i];
-          }
-#pragma unroll
-          for (int i = ks; i < W_LOADS; i += kRounds - 1, ++moves) {
-            gw[u][i] = *reinterpret_cast<const u32x4*>(w_src + w_off[i]);
-            *reinterpret_cast<u32x4*>(&sh_w[cur ^ 1][srow + i * 32][schunk]) = gw[(u + 1) % D][i];
-          }
-          // the order inside the round: an MFMA, then at most one instruction of each kind
-          constexpr int kMfma = JB * IB;
-          constexpr int kMoves = (A_LOADS + kRounds - 2) / (kRounds - 1) + (W_LOADS + kRounds - 2) / (kRounds - 1);
+        for (int ks = 0; ks < kRounds; ++ks) {
+          const bool last = ks + 1 == kRounds;
+          // where the fragments of the next round come from: this stage, or (round 3) the next step's
+          const bf16_t* wsrc = last ? &sh_w[cur ^ 1][wn * 128 + l32][half * 8]
+                                    : &sh_w[cur][wn * 128 + l32][(ks + 1) * 16 + half * 8];
+          const bf16_t* hsrc = last ? &sh_a[cur ^ 1][wm * WM + l32][half * 8]
+                                    : &sh_a[cur][wm * WM + l32][(ks + 1) * 16 + half * 8];
+          // this round's share of the request (set u) and of the LDS writes (set u+1): rows ks,
+          // ks+3, ... of either operand; none in round 3 (behind the barrier)
+          const int nA = (last || ks >= A_LOADS) ? 0 : (A_LOADS - ks + kRounds - 2) / (kRounds - 1);
+          const int nW = (last || ks >= W_LOADS) ? 0 : (W_LOADS - ks + kRounds - 2) / (kRounds - 1);
+          const int nmoves = nA + nW;
 #pragma unroll
           for (int i = 0; i < kMfma; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  // one MFMA
-            if (i < JB + IB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                 // one LDS read
-            if ((i * kMoves) / kMfma != ((i + 1) * kMoves) / kMfma) {
-              __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                // one global load
-              __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                                // one LDS write
-            }
-          }
-          (void)moves;
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        __syncthreads();
-        lm_load_frags<JB>(wf[0], &sh_w[cur ^ 1][wn * 128 + l32][half * 8]);
-        lm_load_frags<IB>(hf[0], &sh_a[cur ^ 1][wm * WM + l32][half * 8]);
-#pragma unroll
-        for (int jb = 0; jb < JB; ++jb)
-#pragma unroll
-          for (int ib = 0; ib < IB; ++ib)
-            acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[(kRounds - 1) & 1][jb]),
-                                                                  __builtin_bit_cast(bf16x8_t, hf[(kRounds - 1) & 1][ib]),
+            const int jb = i / IB, ib = i % IB;
+            acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[ks & 1][jb]),
+                                                                  __builtin_bit_cast(bf16x8_t, hf[ks & 1][ib]),
                                                                   acc[jb][ib], 0, 0, 0);
+            // one fragment of the next round behind each of the first MFMAs
 #pragma unroll
-        for (int i = 0; i < JB * IB; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          if (i < JB + IB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            for (int r = 0; r < JB + IB; ++r)
+              if (min(r, kMfma - 1) == i) {
+                if (r < JB) wf[(ks + 1) & 1][r] = *reinterpret_cast<const u32x4*>(wsrc + r * 32 * kLmStride);
+                else hf[(ks + 1) & 1][r - JB] = *reinterpret_cast<const u32x4*>(hsrc + (r - JB) * 32 * kLmStride);
+              }
+            // a global load and an LDS write behind some of them, none behind the last two (the
+            // barrier after round 2 should not have to wait for an LDS instruction just issued)
+#pragma unroll
+            for (int m = 0; m < nmoves; ++m)
+              if (1 + m * (kMfma - 3) / nmoves == i) {  // slots 1 .. kMfma - 3
+                if (m < nA) {
+                  const int j = ks + m * (kRounds - 1);
+                  ga[u][j] = *reinterpret_cast<const u32x4*>(a_src + a_off[j]);
+                  *reinterpret_cast<u32x4*>(&sh_a[cur ^ 1][srow + j * 32][schunk]) = ga[(u + 1) % D][j];
+                } else {
+                  const int j = ks + (m - nA) * (kRounds - 1);
+                  gw[u][j] = *reinterpret_cast<const u32x4*>(w_src + w_off[j]);
+                  *reinterpret_cast<u32x4*>(&sh_w[cur ^ 1][srow + j * 32][schunk]) = gw[(u + 1) % D][j];
+                }
+              }
+            __builtin_amdgcn_sched_barrier(0);  // keep this order
+          }
+          if (ks + 2 == kRounds) __syncthreads();
         }
-        __builtin_amdgcn_sched_barrier(0);
         MARS_LM_ADVANCE()
       }
     }
