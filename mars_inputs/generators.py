@@ -58,6 +58,15 @@ def random_tree(rng: np.random.Generator, N: int, depth: int, max_children: int)
         return np.array([-1], dtype=np.int32)
     if depth * 1 > N - 1:
         raise ValueError("tree cannot reach the requested depth")
+    capacity, level = 1, 1
+    for _ in range(depth):
+        level *= max_children
+        capacity += level
+        if capacity >= N:
+            break
+    if capacity < N:
+        raise ValueError(f"a tree of depth {depth} with at most {max_children} children per node holds "
+                         f"{capacity} nodes, not {N}")
     while True:
         parent = np.full(N, -1, dtype=np.int32)
         d = np.zeros(N, dtype=np.int32)

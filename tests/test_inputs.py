@@ -66,3 +66,16 @@ def test_dense_draft_distribution_is_a_distribution_and_siblings_differ():
         for p in range(10):
             kids = [w.draft_tokens[b, i] for i in range(1, 10) if w.tree_parent[b, i] == p]
             assert len(set(kids)) == len(kids)
+
+
+def test_random_tree_rejects_shapes_that_cannot_exist():
+    import numpy as np
+    import pytest
+    from mars_inputs import random_tree
+    rng = np.random.default_rng(0)
+    with pytest.raises(ValueError):
+        random_tree(rng, 33, 2, 3)          # 1 + 3 + 9 = 13 nodes at most
+    with pytest.raises(ValueError):
+        random_tree(rng, 5, 7, 2)           # five nodes cannot be seven deep
+    p = random_tree(rng, 13, 2, 3)          # exactly full
+    assert p[0] == -1 and len(p) == 13
