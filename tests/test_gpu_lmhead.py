@@ -79,6 +79,40 @@ def test_shapes(i):
         assert ref["accept_len"].max() >= 1
 
 
+def test_seeded_sweep_of_shapes():
+    """Sixteen shapes drawn from a seed: rows 1 .. 3000, H in {128 .. 2048}, odd and tile-aligned
+    vocabularies, chains and trees, the three indicators, commit outputs included."""
+    rng = np.random.default_rng(20260)
+    for c in range(16):
+        H = int(rng.choice([128, 256, 384, 512, 640, 1024, 2048]))
+        B, N = int(rng.integers(1, 48)), int(rng.integers(1, 64))
+        rows = B * N
+        vmin = 2 * rows + 2
+        V = int(rng.integers(vmin, max(vmin + 1, min(200000, int(2e10 / (rows * H)))) + 1))
+        if rng.random() < 0.3:
+            V = max(vmin, (V // 256) * 256 + int(rng.choice([0, 1, 255])))
+        tree = {"kind": "chain"}
+        if N >= 4 and rng.random() < 0.6:
+            while True:
+                dep, ch = int(rng.integers(2, min(6, N - 1) + 1)), int(rng.integers(2, 5))
+                if sum(ch ** k for k in range(dep + 1)) >= 2 * N:
+                    tree = {"kind": "tree", "depth": dep, "max_children": ch}
+                    break
+        ind = int(rng.choice([0, 0, 1, 2]))
+        thetas = {0: (0.85, 0.9, 0.95), 1: (0.3,), 2: (1.5,)}[ind]
+        say(f"[case] lmhead sweep {c}: B={B} N={N} H={H} V={V} {tree} indicator={ind}")
+        w = make_lmhead_workload(f"sweep{c}", B=B, N=N, H=H, V=V, tree=tree, theta_choices=thetas, seed=500 + c)
+        ref = lmhead_ref.screen_lmhead(w, indicator=ind)
+        d = to_device(w)
+        out = M.mars_lmhead_verify(d["h"], d["w"], d["tok"], d["par"], d["th"], indicator=ind, want_commit=True)
+        torch.cuda.synchronize()
+        assert_rows_match(out.stats, ref["stats"], f"sweep {c}")
+        assert_requests_match(out, ref, f"sweep {c}")
+        want = mars_ref.commit(w.draft_tokens, ref["accept_len"], ref["path_idx"], ref["bonus_token"])
+        for key in ("out_tokens", "out_len", "keep_rows", "keep_offsets"):
+            assert np.array_equal(getattr(out, key).cpu().numpy(), want[key]), (c, key)
+
+
 def test_per_request_thresholds_and_other_indicators():
     shape = dict(B=8, N=16, H=256, V=12000, tree={"kind": "tree", "depth": 4, "max_children": 3})
     run_case("thetas", theta_choices=(0.85, 0.9, 0.95), seed=21, **shape)
