@@ -117,11 +117,11 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
   for (int i = 0; i < W_LOADS; ++i)
     w_off[i] = static_cast<unsigned int>(min(V - 1 - l_tile * kLmBN, srow + i * 32)) * H + schunk;
 
-  // (Unconditional on purpose: with a request under a branch the compiler has to place its
-  // s_waitcnt for the case that nothing was issued, which makes every step wait for the loads it
-  // has just sent.  Past the end of the run the last slab is simply requested again.  The
-  // bookkeeping with its branch is kept apart, so that the loads share a scheduling region with
-  // the matrix instructions they are interleaved with.)
+  // (Requests are unconditional on purpose: with a request under a branch the compiler has to
+  // place its s_waitcnt for the case that nothing was issued, which makes every step wait for the
+  // loads it has just sent.  Past the end of the run the last slab is simply requested again.
+  // The bookkeeping with its branch is kept apart from the loads, which the steps below issue one
+  // by one between their matrix instructions.)
 #define MARS_LM_REQUEST(SET)                                                                        \
   {                                                                                                 \
     lm_load_global<A_LOADS>(ga[SET], a_tile, a_off, l_kt * kLmBK);                                  \
@@ -166,8 +166,9 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
         const int cur = step & 1;
         // Four 16-deep multiplication rounds of twelve MFMAs.  A wave is alone on its SIMD, so
         // nothing hides a memory instruction's issue time or an LDS round trip but its own matrix
-        // instructions: every memory instruction of the step is slotted between two MFMAs
-        // (sched_group_barrier pins that order).  Rounds 0..2: the fragments of the next round
+        // instructions: every memory instruction of the step is slotted between two MFMAs (the
+        // code is written in that order and a scheduling barrier behind every MFMA keeps the
+        // compiler from regrouping it).  Rounds 0..2: the fragments of the next round
         // (7 LDS reads), the step's operand request for two steps ahead (set u held this step's
         // operands, which are in LDS by now: 14 global loads) and the operands of the next step
         // (set u+1, requested a step ago: 14 LDS writes into the other stage).  The step's only
