@@ -130,4 +130,6 @@ LMHEAD_CONFIGS = {
     "small": dict(name="lmhead_small", B=4, N=9, H=256, V=5000, tree={"kind": "chain"}, plant_frac=0.6),
     "headline": dict(name="lmhead_B16_tree60_H4096_V151936", B=16, N=60, H=4096, V=151936,
                      tree={"kind": "tree", "depth": 6, "max_children": 4}, plant_frac=0.6),
+    "chains": dict(name="lmhead_B64_chain8_H4096_V128256", B=64, N=9, H=4096, V=128256,
+                   tree={"kind": "chain"}, plant_frac=0.6, theta_choices=(0.85, 0.9, 0.95)),
 }

@@ -189,6 +189,37 @@ def test_calls_on_two_streams_and_repeated_calls_agree():
         assert_rows_match(out.stats, ref["stats"], f"call {i}")
 
 
+def test_chain_batch_shape_sampled_requests():
+    """B = 64 chains of 8 drafts, H = 4096, V = 128 256, per-request thresholds (three slabs of 192 rows):
+    eight requests against the oracle, the others through what holds for any input."""
+    spec = dict(LMHEAD_CONFIGS["chains"])
+    name = spec.pop("name")
+    say(f"[case] lmhead {name}: generating")
+    w = make_lmhead_workload(name, seed=9, **spec)
+    pick = [0, 5, 21, 22, 40, 41, 62, 63]
+    say("[case] oracle on eight requests")
+    ref = lmhead_ref.screen_lmhead(w, requests=pick)
+    d = to_device(w)
+    out = M.mars_lmhead_verify(d["h"], d["w"], d["tok"], d["par"], d["th"], want_commit=True)
+    torch.cuda.synchronize()
+    rows = (np.asarray(pick)[:, None] * w.N + np.arange(w.N)[None, :]).reshape(-1)
+    assert_rows_match(out.stats.view(-1, M.ROW_STAT_WORDS)[torch.from_numpy(rows).to(DEV)], ref["stats"], name)
+    assert_requests_match(out, ref, name, pick=pick)
+    s = {k: v.cpu().numpy().reshape(w.B, w.N) for k, v in M.unpack_stats(out.stats).items()}
+    alen, bonus = out.accept_len.cpu().numpy(), out.bonus_token.cpu().numpy()
+    out_tok, out_len = out.out_tokens.cpu().numpy(), out.out_len.cpu().numpy()
+    assert (out.request_status.cpu().numpy() == 0).all()
+    for b in range(w.B):          # a chain: accepted nodes are 1 .. alen, then the top-1 of the last node's row
+        for k in range(1, alen[b] + 1):
+            assert w.draft_tokens[b, k] in (s["id1"][b, k - 1], s["id2"][b, k - 1])
+        if alen[b] + 1 < w.N:       # the next draft was rejected
+            t, p = w.draft_tokens[b, alen[b] + 1], alen[b]
+            assert t != s["id1"][b, p] and not (t == s["id2"][b, p] and s["relax_ok"][b, p])
+        assert bonus[b] == s["id1"][b, alen[b]] and out_len[b] == alen[b] + 1
+        assert list(out_tok[b, :alen[b]]) == list(w.draft_tokens[b, 1:alen[b] + 1]) and out_tok[b, alen[b]] == bonus[b]
+    assert alen.max() >= 3
+
+
 def test_headline_shape_sampled_requests():
     """B = 16 trees of 60 nodes, H = 4096, V = 151 936 in the launch shape the benchmark times: three
     requests are checked in full against the oracle (their rows screened), the others through what
