@@ -189,6 +189,56 @@ def test_calls_on_two_streams_and_repeated_calls_agree():
         assert_rows_match(out.stats, ref["stats"], f"call {i}")
 
 
+def test_two_parts_of_a_call_and_graph_replays():
+    """options.stages splits the call into the fused LM-head kernel and the per-request part; and the
+    call only enqueues kernels, so a HIP graph may hold it: replays with the hidden states changed under
+    the graph equal eager calls on the same inputs."""
+    ws_host = [make_lmhead_workload("g0", B=5, N=20, H=256, V=20000, tree={"kind": "tree", "depth": 4, "max_children": 3}, seed=71),
+               make_lmhead_workload("g1", B=5, N=20, H=256, V=20000, tree={"kind": "tree", "depth": 4, "max_children": 3}, seed=72)]
+    refs = [lmhead_ref.screen_lmhead(w) for w in ws_host]
+    devs = [to_device(w) for w in ws_host]
+    B, N, H, V = ws_host[0].B, ws_host[0].N, ws_host[0].H, ws_host[0].V
+    cur = {k: v.clone() for k, v in devs[0].items()}
+    ws = torch.empty(M.mars_lmhead_workspace_bytes(B, N, V, H), dtype=torch.uint8, device=DEV)
+    out_g = M.VerifyOutputs(B, N, DEV, want_diag=False, want_commit=True)
+    out_s = M.VerifyOutputs(B, N, DEV, want_diag=False, want_commit=True)
+
+    # the two parts one after the other
+    M.mars_lmhead_verify(cur["h"], cur["w"], cur["tok"], cur["par"], cur["th"], out_s, ws, stages=M.MARS_STAGE_ROWS)
+    M.mars_lmhead_verify(cur["h"], cur["w"], cur["tok"], cur["par"], cur["th"], out_s, ws, stages=M.MARS_STAGE_REQUESTS)
+    torch.cuda.synchronize()
+    assert_requests_match(out_s, refs[0], "two parts")
+    assert_rows_match(out_s.stats, refs[0]["stats"], "two parts")
+
+    def call(out):
+        M.mars_lmhead_verify(cur["h"], cur["w"], cur["tok"], cur["par"], cur["th"], out, ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call(out_g)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call(out_g)
+    for rep in range(4):
+        for k, v in cur.items():
+            v.copy_(devs[rep % 2][k])
+        for key in ("accept_len", "bonus_token", "path_idx", "out_tokens", "keep_rows"):
+            getattr(out_g, key).fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_requests_match(out_g, refs[rep % 2], f"replay {rep}")
+        assert_rows_match(out_g.stats, refs[rep % 2]["stats"], f"replay {rep}")
+        want = mars_ref.commit(ws_host[rep % 2].draft_tokens, refs[rep % 2]["accept_len"], refs[rep % 2]["path_idx"],
+                               refs[rep % 2]["bonus_token"])
+        for key in ("out_tokens", "out_len", "keep_rows", "keep_offsets"):
+            assert np.array_equal(getattr(out_g, key).cpu().numpy(), want[key]), (rep, key)
+        torch.ones(1000, device=DEV).sum().item()        # eager work between the replays
+
+
 def test_chain_batch_shape_sampled_requests():
     """B = 64 chains of 8 drafts, H = 4096, V = 128 256, per-request thresholds (three slabs of 192 rows):
     eight requests against the oracle, the others through what holds for any input."""
