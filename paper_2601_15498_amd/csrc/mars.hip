@@ -179,7 +179,7 @@ static bool lm_sizes_ok(int B, int N, int V, int H, int K) {
 
 extern "C" {
 
-int mars_version(void) { return 100; }
+int mars_version(void) { return 200; }  // 0.2.0: mars_lmhead_verify
 
 const char* mars_status_string(int status) {
   switch (status) {
