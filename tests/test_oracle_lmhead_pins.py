@@ -192,6 +192,17 @@ def test_screening_leaves_every_row_clear():
     assert np.all((np.abs(ratio - w.theta[:, None]) >= 1e-4) | (z1 <= 0))
 
 
+def test_screening_a_sub_batch_describes_those_requests():
+    w = small(seed=9, B=6)
+    sub = lmhead_ref.screen_lmhead(w, clearance=1e-3, requests=[4, 1])
+    assert sub["clearance"].min() >= 1e-3 and sub["accept_len"].shape == (2,)
+    full = lmhead_ref.lmhead_verify(w.hidden, w.weight, w.draft_tokens, w.tree_parent, w.theta)   # after the redraws
+    for key in ("accept_len", "bonus_token", "path_idx", "decision"):
+        assert np.array_equal(sub[key], full[key][[4, 1]]), key
+    assert np.array_equal(sub["stats"]["id1"], full["stats"]["id1"][[4, 1]])
+    assert np.array_equal(sub["exact"], full["exact"].reshape(6, w.N, w.V)[[4, 1]].reshape(-1, w.V))
+
+
 def test_generator_rejects_a_vocabulary_too_small_for_its_rows():
     with pytest.raises(ValueError):
         make_lmhead_workload("x", B=2, N=5, H=64, V=20, tree={"kind": "chain"})
