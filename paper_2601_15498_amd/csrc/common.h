@@ -249,13 +249,14 @@ __device__ __forceinline__ unsigned long long dpp_move(unsigned long long v) {
 // when a row has at most sixteen), and a butterfly inside the DPP row merges keys and sums.
 // Every lane of the sixteen ends with the row's result; lane 0 of them hands it to `emit`.
 // Must be called by all NT threads of the work-group (NT a multiple of 64).
-constexpr int kMergeBatch = 4;  // partial results a lane has in flight at a time
+constexpr int kMergeBatch = 4;  // partial results a lane has in flight at a time (a kernel with registers to spare: 8)
 // Partial results s0, s0 + 16, ... of one row (empty ones past the end, or for a row that does not exist).
+template <int BATCH>
 __device__ __forceinline__ void load_partials(const Partial* __restrict__ partials, int row, int nrows, int parts,
-                                              int s0, Partial (&q)[kMergeBatch]) {
+                                              int s0, Partial (&q)[BATCH]) {
   const Partial* __restrict__ p = partials + static_cast<size_t>(row) * parts;
 #pragma unroll
-  for (int j = 0; j < kMergeBatch; ++j) {
+  for (int j = 0; j < BATCH; ++j) {
     const int s = s0 + 16 * j;
     if (row < nrows && s < parts) {
       q[j] = p[s];
@@ -264,25 +265,26 @@ __device__ __forceinline__ void load_partials(const Partial* __restrict__ partia
     }
   }
 }
-__device__ __forceinline__ void fold_partials(const Partial (&q)[kMergeBatch], float c, unsigned long long& k1,
+template <int BATCH>
+__device__ __forceinline__ void fold_partials(const Partial (&q)[BATCH], float c, unsigned long long& k1,
                                               unsigned long long& k2, float& R, double& S) {
 #pragma unroll
-  for (int j = 0; j < kMergeBatch; ++j) {
+  for (int j = 0; j < BATCH; ++j) {
     if (q[j].id1 >= 0) top2_insert(k1, k2, make_key(q[j].z1, q[j].id1));
     if (q[j].id2 >= 0) top2_insert(k1, k2, make_key(q[j].z2, q[j].id2));
     if (c > 0.0f && q[j].s > 0.0f) absorb_sum(R, S, q[j].ref, static_cast<double>(q[j].s));
   }
 }
 
-template <int NT, typename ThetaAt, typename Emit>
+template <int NT, int BATCH = kMergeBatch, typename ThetaAt, typename Emit>
 __device__ __forceinline__ void merge_rows_coop(const Partial* __restrict__ partials, int nrows, int parts,
                                                 float c, const Indicator& ind, ThetaAt theta_at, Emit emit) {
   const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
   constexpr int kGroups = NT / 16;
-  // A lane has kMergeBatch loads in flight at a time, and the first batch of the next pass over the
+  // A lane has BATCH loads in flight at a time, and the first batch of the next pass over the
   // rows is requested before the current pass is worked on: merging N rows costs about one memory
   // round trip, not one per pass.
-  Partial nxt[kMergeBatch];
+  Partial nxt[BATCH];
   load_partials(partials, grp, nrows, parts, sub, nxt);
   for (int row0 = 0; row0 < nrows; row0 += kGroups) {
     const int row = row0 + grp;
@@ -290,12 +292,12 @@ __device__ __forceinline__ void merge_rows_coop(const Partial* __restrict__ part
     unsigned long long k1 = 0, k2 = 0;
     float R = -3.0e38f;
     double S = 0.0;
-    Partial cur[kMergeBatch];
+    Partial cur[BATCH];
 #pragma unroll
-    for (int j = 0; j < kMergeBatch; ++j) cur[j] = nxt[j];
+    for (int j = 0; j < BATCH; ++j) cur[j] = nxt[j];
     load_partials(partials, row + kGroups, nrows, parts, sub, nxt);
     fold_partials(cur, c, k1, k2, R, S);
-    for (int s0 = sub + 16 * kMergeBatch; s0 < parts; s0 += 16 * kMergeBatch) {
+    for (int s0 = sub + 16 * BATCH; s0 < parts; s0 += 16 * BATCH) {
       load_partials(partials, row, nrows, parts, s0, cur);
       fold_partials(cur, c, k1, k2, R, S);
     }

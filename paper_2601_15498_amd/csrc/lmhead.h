@@ -271,22 +271,37 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
 #undef MARS_LM_REQUEST
 #undef MARS_LM_ADVANCE
 
-  // Lanes l and l + 32 hold the same rows (different vocabulary entries): combine, and the lower
-  // half writes the partial result of (row, run, wave column).
-  const int parts = runs * 2;
+  // Lanes l and l + 32 hold the same rows (different vocabulary entries), and so do the two waves
+  // side by side (wn = 0, 1): the half-waves combine through a lane exchange, the waves through LDS
+  // (the operand stages are free by now), and wave column 0 writes the one partial result of
+  // (row, run).
+  __syncthreads();  // every wave is done with the operand stages
+  unsigned long long* xch = reinterpret_cast<unsigned long long*>(&sh_a[0][0][0]);  // [wm][ib][32 rows][2 keys]
+  unsigned long long r1[IB], r2[IB];
 #pragma unroll
   for (int ib = 0; ib < IB; ++ib) {
     const unsigned long long o1 = __shfl_xor(best1[ib], 32, kWave), o2 = __shfl_xor(best2[ib], 32, kWave);
-    unsigned long long k1 = best1[ib], k2 = best2[ib];
-    top2_insert(k1, k2, o1);
-    top2_insert(k1, k2, o2);
+    r1[ib] = best1[ib]; r2[ib] = best2[ib];
+    top2_insert(r1[ib], r2[ib], o1);
+    top2_insert(r1[ib], r2[ib], o2);
+    if (wn == 1 && half == 0) {
+      xch[((wm * IB + ib) * 32 + l32) * 2 + 0] = r1[ib];
+      xch[((wm * IB + ib) * 32 + l32) * 2 + 1] = r2[ib];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int ib = 0; ib < IB; ++ib) {
     const int row = m0 + wm * WM + ib * 32 + l32;
-    if (half == 0 && row < M) {
+    if (wn == 0 && half == 0 && row < M) {
+      unsigned long long k1 = r1[ib], k2 = r2[ib];
+      top2_insert(k1, k2, xch[((wm * IB + ib) * 32 + l32) * 2 + 0]);
+      top2_insert(k1, k2, xch[((wm * IB + ib) * 32 + l32) * 2 + 1]);
       Partial out;
       out.z1 = neg_inf(); out.id1 = -1; out.z2 = neg_inf(); out.id2 = -1; out.s = 0.0f; out.ref = 0.0f;
       if (k1 != 0ull) { out.z1 = key_value(k1); out.id1 = key_index(k1); }
       if (k2 != 0ull) { out.z2 = key_value(k2); out.id2 = key_index(k2); }
-      partials[static_cast<size_t>(row) * parts + run * 2 + wn] = out;
+      partials[static_cast<size_t>(row) * runs + run] = out;
     }
   }
 }

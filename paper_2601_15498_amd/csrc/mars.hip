@@ -153,7 +153,7 @@ static LmPlan lm_plan(long rows, int V) {
   if (want > p.tiles_n) want = p.tiles_n;
   p.tiles_per_run = (p.tiles_n + want - 1) / want;
   p.runs = (p.tiles_n + p.tiles_per_run - 1) / p.tiles_per_run;
-  p.parts = 2 * p.runs;
+  p.parts = p.runs;  // one partial result per (row, run)
   return p;
 }
 

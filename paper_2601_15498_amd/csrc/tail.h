@@ -60,7 +60,9 @@ __device__ int merge_and_validate(const TailArgs& a, int b, bool write_user_stat
   const size_t rb = static_cast<size_t>(b) * N;
   const size_t rd = static_cast<size_t>(b % a.Bd) * N;  // where the request's inputs are
   const float theta = a.theta[b];
-  merge_rows_coop<NT>(a.partials + rd * a.splits, N, a.splits, a.c, a.ind, [&](int) { return theta; },
+  // (eight loads in flight per lane: this kernel has the registers, and behind the fused LM head a
+  // row has up to a few hundred partial results)
+  merge_rows_coop<NT, 8>(a.partials + rd * a.splits, N, a.splits, a.c, a.ind, [&](int) { return theta; },
                       [&](int row, const mars_row_stat& st) {
                         // Several work-groups of a request may write the workspace copy: identical bits.
                         a.stats_ws[rb + row] = st;
