@@ -65,11 +65,33 @@ WORKLOADS = {
 }
 
 
+def _code_only(text: str) -> str:
+    """C++ source with its comments taken out and runs of white space collapsed (string literals
+    are left alone): what a counter capture is tied to is the code, not its commentary."""
+    out, i, n = [], 0, len(text)
+    while i < n:
+        c = text[i]
+        if c == '"' or c == "'":
+            j = i + 1
+            while j < n and text[j] != c:
+                j += 2 if text[j] == "\\" else 1
+            out.append(text[i:j + 1]); i = j + 1
+        elif text.startswith("//", i):
+            j = text.find("\n", i)
+            i = n if j < 0 else j
+        elif text.startswith("/*", i):
+            j = text.find("*/", i + 2)
+            out.append(" "); i = n if j < 0 else j + 2
+        else:
+            out.append(c); i += 1
+    return " ".join("".join(out).split())
+
+
 def kernel_source_digest(files=("common.h", "row_reduce.h")) -> str:
     h = hashlib.sha256()
     for f in files:
-        with open(os.path.join(ROOT, "paper_2601_15498_amd", "csrc", f), "rb") as fh:
-            h.update(fh.read())
+        with open(os.path.join(ROOT, "paper_2601_15498_amd", "csrc", f), "r", encoding="utf-8") as fh:
+            h.update(_code_only(fh.read()).encode("utf-8"))
     return h.hexdigest()[:16]
 
 

@@ -323,6 +323,10 @@ int mars_margin_stats(const void* logits, int logits_dtype, const float* theta, 
  * defined as the fp32-accumulated products rounded once to bf16 (what a bf16 LM head hands to the
  * verifier); everything behind them -- low-margin test, Alg. 1 on a chain or tree, committed
  * sequence, sweep over thresholds -- is mars_verify_ex in greedy mode.
+ * The order in which a row's products are added is the kernel's own and depends on the launch
+ * plan (so on B*N and V): a logit whose exact value lies within the fp32 accumulation error of a
+ * bf16 rounding boundary may come out one bf16 step apart between two batch shapes; for one shape
+ * the result is reproducible bit for bit.
  *
  *   hidden   device, [B,N,H] bf16, 16-byte aligned: last hidden state of every node.
  *   weight   device, [V,H] bf16, 16-byte aligned: the LM head, one row per vocabulary entry.

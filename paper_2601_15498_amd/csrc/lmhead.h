@@ -10,8 +10,9 @@
 // each accumulate (BM/2) x 128 logits with v_mfma_f32_32x32x16_bf16.  The weight rows are the
 // first MFMA operand and the hidden states the second, so that a lane ends up holding, for one
 // hidden-state row, 16 vocabulary entries per accumulator block: the row's top-2 over the wave's
-// 128 entries is taken inside the lane, the two halves of the wave that share a row meet once at
-// the very end, and a running pair per row is carried across the tiles of the run.
+// 128 entries is taken inside the lane, a running pair per row is carried across the tiles of the
+// run, and the two halves of a wave and the two waves that share a row meet once at the very end:
+// one partial result per (row, run).
 #pragma once
 
 #include "common.h"
