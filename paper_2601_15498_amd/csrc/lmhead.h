@@ -154,8 +154,8 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
   lm_store_lds<A_LOADS>(ga[0], &sh_a[0][srow][schunk]);
   lm_store_lds<W_LOADS>(gw[0], &sh_w[0][srow][schunk]);
   __syncthreads();
-  // operand fragments of the current and the next round (lane l: row l%32 of its block,
-  // elements 8*(l/32) .. +7 of the 16-deep round)
+  // operand fragments of the current and the next quarter (lane l: row l%32 of its block,
+  // elements 8*(l/32) .. +7 of the 16-deep quarter)
   u32x4 wf[2][JB], hf[2][IB];
   lm_load_frags<JB>(wf[0], &sh_w[0][wn * 128 + l32][half * 8]);
   lm_load_frags<IB>(hf[0], &sh_a[0][wm * WM + l32][half * 8]);
@@ -174,31 +174,31 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
 #pragma unroll
       for (int u = 0; u < D; ++u, ++step) {
         const int cur = step & 1;
-        // Four 16-deep multiplication rounds of twelve MFMAs.  A wave is alone on its SIMD, so
+        // Four 16-deep multiplication quarters of twelve MFMAs.  A wave is alone on its SIMD, so
         // nothing hides a memory instruction's issue time or an LDS round trip but its own matrix
         // instructions: every memory instruction of the step is slotted between two MFMAs (the
         // code is written in that order and a scheduling barrier behind every MFMA keeps the
-        // compiler from regrouping it).  Rounds 0..2: the fragments of the next round
+        // compiler from regrouping it).  Quarters 0..2: the fragments of the next quarter
         // (7 LDS reads), the step's operand request for two steps ahead (set u held this step's
         // operands, which are in LDS by now: 14 global loads) and the operands of the next step
         // (set u+1, requested a step ago: 14 LDS writes into the other stage).  The step's only
-        // barrier follows round 2 -- by then this stage has been read for the last time (round
-        // 3's fragments are in registers) and the other one is complete -- so that round 3 can
+        // barrier follows quarter 2 -- by then this stage has been read for the last time (quarter
+        // 3's fragments are in registers) and the other one is complete -- so that quarter 3 can
         // already fetch the next step's first fragments.
         constexpr int kRounds = kLmBK / 16;
-        constexpr int kMfma = JB * IB;  // MFMAs per round
+        constexpr int kMfma = JB * IB;  // MFMAs per quarter
         const bf16_t* __restrict__ a_src = a_tile + l_kp * kLmBK;
         const bf16_t* __restrict__ w_src = w_tile + l_kp * kLmBK;
 #pragma unroll
         for (int ks = 0; ks < kRounds; ++ks) {
           const bool last = ks + 1 == kRounds;
-          // where the fragments of the next round come from: this stage, or (round 3) the next step's
+          // where the fragments of the next quarter come from: this stage, or (quarter 3) the next step's
           const bf16_t* wsrc = last ? &sh_w[cur ^ 1][wn * 128 + l32][half * 8]
                                     : &sh_w[cur][wn * 128 + l32][(ks + 1) * 16 + half * 8];
           const bf16_t* hsrc = last ? &sh_a[cur ^ 1][wm * WM + l32][half * 8]
                                     : &sh_a[cur][wm * WM + l32][(ks + 1) * 16 + half * 8];
-          // this round's share of the request (set u) and of the LDS writes (set u+1): rows ks,
-          // ks+3, ... of either operand; none in round 3 (behind the barrier)
+          // this quarter's share of the request (set u) and of the LDS writes (set u+1): rows ks,
+          // ks+3, ... of either operand; none in quarter 3 (behind the barrier)
           const int nA = (last || ks >= A_LOADS) ? 0 : (A_LOADS - ks + kRounds - 2) / (kRounds - 1);
           const int nW = (last || ks >= W_LOADS) ? 0 : (W_LOADS - ks + kRounds - 2) / (kRounds - 1);
           const int nmoves = nA + nW;
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
             acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[ks & 1][jb]),
                                                                   __builtin_bit_cast(bf16x8_t, hf[ks & 1][ib]),
                                                                   acc[jb][ib], 0, 0, 0);
-            // one fragment of the next round behind each of the first MFMAs
+            // one fragment of the next quarter behind each of the first MFMAs
 #pragma unroll
             for (int r = 0; r < JB + IB; ++r)
               if (min(r, kMfma - 1) == i) {
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
                 else hf[(ks + 1) & 1][r - JB] = *reinterpret_cast<const u32x4*>(hsrc + (r - JB) * 32 * kLmStride);
               }
             // a global load and an LDS write behind some of them, none behind the last two (the
-            // barrier after round 2 should not have to wait for an LDS instruction just issued)
+            // barrier after quarter 2 should not have to wait for an LDS instruction just issued)
 #pragma unroll
             for (int m = 0; m < nmoves; ++m)
               if (1 + m * (kMfma - 3) / nmoves == i) {  // slots 1 .. kMfma - 3
