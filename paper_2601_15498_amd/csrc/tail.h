@@ -51,41 +51,10 @@ struct TailArgs {
   unsigned long long* xslots;  // [B][N+2][G][2] tagged exchange words, cleared by the row reduction
 };
 
-// ---------------------------------------------------------------- steps shared by both modes
-// Merge this request's rows, validate tree and tokens.  Returns the request status
-// (uniform over the work-group).  Ends with a barrier: stats of the request are visible.
-template <int NT>
-__device__ int merge_and_validate(const TailArgs& a, int b, bool write_user_stats) {
-  const int N = a.N;
-  const size_t rb = static_cast<size_t>(b) * N;
-  const size_t rd = static_cast<size_t>(b % a.Bd) * N;  // where the request's inputs are
-  const float theta = a.theta[b];
-  // (eight loads in flight per lane: this kernel has the registers, and behind the fused LM head a
-  // row has up to a few hundred partial results)
-  merge_rows_coop<NT, 8>(a.partials + rd * a.splits, N, a.splits, a.c, a.ind, [&](int) { return theta; },
-                      [&](int row, const mars_row_stat& st) {
-                        // Several work-groups of a request may write the workspace copy: identical bits.
-                        a.stats_ws[rb + row] = st;
-                        if (write_user_stats && a.stats) a.stats[rb + row] = st;
-                      });
-  int bad = 0;
-  for (int i = threadIdx.x; i < N; i += NT) {
-    const int p = a.par[rd + i];
-    const int t = a.tok[rd + i];
-    if (i == 0) { if (p != -1) bad |= 1; }
-    else {
-      if (p < 0 || p >= i) bad |= 1;
-      if (t < 0 || t >= a.V) bad |= 2;
-    }
-  }
-  const int any_tree = __syncthreads_or(bad & 1);
-  const int any_tok = __syncthreads_or(bad & 2);
-  return any_tree ? MARS_REQ_BAD_TREE : (any_tok ? MARS_REQ_BAD_TOKEN : MARS_REQ_OK);
-}
-
+// ---------------------------------------------------------------- shared by both modes
 // Outputs of a request that failed validation: nothing accepted, token = v(1) of the root row.
 template <int NT>
-__device__ void write_rejected_request(const TailArgs& a, int b, int status) {
+__device__ void write_rejected_request(const TailArgs& a, int b, int status, int root_top1) {
   const int N = a.N;
   for (int i = threadIdx.x; i < N; i += NT) {
     const size_t r = static_cast<size_t>(b) * N + i;
@@ -96,38 +65,71 @@ __device__ void write_rejected_request(const TailArgs& a, int b, int status) {
   }
   if (threadIdx.x == 0) {
     a.len[b] = 0;
-    a.bonus[b] = a.stats_ws[static_cast<size_t>(b) * N].id1;
-    if (a.out_tok) { a.out_tok[static_cast<size_t>(b) * N] = a.stats_ws[static_cast<size_t>(b) * N].id1; a.out_len[b] = 1; }
+    a.bonus[b] = root_top1;
+    if (a.out_tok) { a.out_tok[static_cast<size_t>(b) * N] = root_top1; a.out_len[b] = 1; }
     if (a.status) a.status[b] = status;
     if (a.diag) { mars_req_diag d = {0.0f, 0.0f, 0, 0}; a.diag[b] = d; }
   }
 }
 
 // ---------------------------------------------------------------- greedy mode
+// The kernel is a chain of latencies, so it makes one trip to memory: the tree and the tokens are
+// requested ahead of the partial results, the merged rows go to the caller's table and, for the
+// kernel's own use, to LDS, and everything after that -- decisions, reachability, the walk back
+// along the accepted path -- reads LDS only.
 __global__ __launch_bounds__(kGreedyThreads) void tail_greedy_kernel(TailArgs a) {
   constexpr int NT = kGreedyThreads;
+  static_assert(MARS_MAX_NODES <= NT, "a thread holds the parent and the token of one node");
   __shared__ uint8_t sh_code[MARS_MAX_NODES];
   __shared__ uint8_t sh_ok[2][MARS_MAX_NODES];
   __shared__ int16_t sh_anc[2][MARS_MAX_NODES];
   __shared__ int16_t sh_dep[2][MARS_MAX_NODES];
+  __shared__ int16_t sh_par[MARS_MAX_NODES];
+  __shared__ int32_t sh_tok[MARS_MAX_NODES];
+  __shared__ int32_t sh_top1[MARS_MAX_NODES];    // v(1) of the node's row
+  __shared__ int32_t sh_relax[MARS_MAX_NODES];   // v(2) of the node's row where its low-margin test holds, else -1
   __shared__ unsigned int sh_best;
 
   const int b = blockIdx.x;
   const int N = a.N;
+  const int i = threadIdx.x;
   const size_t rb = static_cast<size_t>(b) * N;
-  const size_t rd = static_cast<size_t>(b % a.Bd) * N;
-  const int status = merge_and_validate<NT>(a, b, true);
-  if (status != MARS_REQ_OK) { write_rejected_request<NT>(a, b, status); return; }
+  const size_t rd = static_cast<size_t>(b % a.Bd) * N;  // where the request's inputs are
+  int p = -1, t = 0;
+  if (i < N) { p = a.par[rd + i]; t = a.tok[rd + i]; }
+  const float theta = a.theta[b];
+  // (eight loads in flight per lane: this kernel has the registers, and behind the fused LM head a
+  // row has up to a few hundred partial results)
+  merge_rows_coop<NT, 8>(a.partials + rd * a.splits, N, a.splits, a.c, a.ind, [&](int) { return theta; },
+                         [&](int row, const mars_row_stat& st) {
+                           a.stats_ws[rb + row] = st;
+                           if (a.stats) a.stats[rb + row] = st;
+                           sh_top1[row] = st.id1;
+                           sh_relax[row] = st.relax_ok ? st.id2 : -1;
+                         });
+  int bad = 0;
+  if (i < N) {
+    if (i == 0) { if (p != -1) bad |= 1; }
+    else {
+      if (p < 0 || p >= i) bad |= 1;
+      if (t < 0 || t >= a.V) bad |= 2;
+    }
+    sh_par[i] = static_cast<int16_t>(p);
+    sh_tok[i] = t;
+  }
+  if (i == 0) sh_best = 0;
+  if (__syncthreads_or(bad)) {  // (the barrier also publishes what the merge left in LDS)
+    const int any_tree = __syncthreads_or(bad & 1);
+    write_rejected_request<NT>(a, b, any_tree ? MARS_REQ_BAD_TREE : MARS_REQ_BAD_TOKEN, sh_top1[0]);
+    return;
+  }
 
   // Local decision of every node against its parent's row (Alg. 1 if-chain).
-  for (int i = threadIdx.x; i < N; i += NT) {
+  if (i < N) {
     int code = 0, anc = 0, dep = 0;
     if (i > 0) {
-      const int p = a.par[rd + i];
-      const int t = a.tok[rd + i];
-      const mars_row_stat st = a.stats_ws[rb + p];
-      if (t == st.id1) code = MARS_DEC_EXACT;
-      else if (t == st.id2 && st.relax_ok) code = MARS_DEC_RELAXED;
+      if (t == sh_top1[p]) code = MARS_DEC_EXACT;
+      else if (t == sh_relax[p]) code = MARS_DEC_RELAXED;  // (t >= 0: never equal to the -1 of a failed test)
       anc = p; dep = 1;
     }
     sh_code[i] = static_cast<uint8_t>(code);
@@ -135,14 +137,13 @@ __global__ __launch_bounds__(kGreedyThreads) void tail_greedy_kernel(TailArgs a)
     sh_anc[0][i] = static_cast<int16_t>(anc);
     sh_dep[0][i] = static_cast<int16_t>(dep);
   }
-  if (threadIdx.x == 0) sh_best = 0;
   __syncthreads();
   // Pointer jumping: after round k, anc is the 2^k-th ancestor (or the root), dep the number
   // of edges to it and ok the AND of the local decisions along those edges.
   int cur = 0;
   for (int span = 1; span < N; span <<= 1) {
     const int nxt = cur ^ 1;
-    for (int i = threadIdx.x; i < N; i += NT) {
+    if (i < N) {
       const int an = sh_anc[cur][i];
       sh_ok[nxt][i] = sh_ok[cur][i] & sh_ok[cur][an];
       sh_dep[nxt][i] = static_cast<int16_t>(sh_dep[cur][i] + sh_dep[cur][an]);
@@ -152,18 +153,15 @@ __global__ __launch_bounds__(kGreedyThreads) void tail_greedy_kernel(TailArgs a)
     __syncthreads();
   }
   // Deepest reachable node, lowest index on ties: max of (depth << 16 | (0xFFFF - i)).
-  unsigned int best = 0;
-  for (int i = threadIdx.x; i < N; i += NT)
-    if (sh_ok[cur][i]) best = max(best, (static_cast<unsigned int>(sh_dep[cur][i]) << 16) | (0xFFFFu - i));
-  atomicMax(&sh_best, best);
-  for (int i = threadIdx.x; i < N; i += NT) {
+  if (i < N) {
+    if (sh_ok[cur][i]) atomicMax(&sh_best, (static_cast<unsigned int>(sh_dep[cur][i]) << 16) | (0xFFFFu - i));
     a.mask[rb + i] = i == 0 ? 1 : 0;
     a.path[rb + i] = -1;
     if (a.dec) a.dec[rb + i] = 0;
     if (a.out_tok) a.out_tok[rb + i] = -1;
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
+  if (i == 0) {
     const unsigned int bk = sh_best;
     const int e = 0xFFFF - static_cast<int>(bk & 0xFFFFu);
     const int L = static_cast<int>(bk >> 16);
@@ -172,11 +170,11 @@ __global__ __launch_bounds__(kGreedyThreads) void tail_greedy_kernel(TailArgs a)
       a.mask[rb + n] = 1;
       a.path[rb + d - 1] = n;
       if (a.dec) a.dec[rb + n] = sh_code[n];
-      if (a.out_tok) a.out_tok[rb + d - 1] = a.tok[rd + n];  // V_out: the accepted drafts ...
-      n = a.par[rd + n];
+      if (a.out_tok) a.out_tok[rb + d - 1] = sh_tok[n];  // V_out: the accepted drafts ...
+      n = sh_par[n];
     }
     a.len[b] = L;
-    const int correction = a.stats_ws[rb + e].id1;  // correction after a rejection, bonus after a leaf
+    const int correction = sh_top1[e];  // correction after a rejection, bonus after a leaf
     a.bonus[b] = correction;
     if (a.out_tok) { a.out_tok[rb + L] = correction; a.out_len[b] = L + 1; }  // ... then this token
     if (a.status) a.status[b] = MARS_REQ_OK;
@@ -526,7 +524,7 @@ __global__ __launch_bounds__(RESIDENT ? kSamplingThreads : kStreamingThreads) vo
   }
   __syncthreads();
   if (sh_bad != 0) {
-    if (g == 0) write_rejected_request<NT>(a, b, (sh_bad & 1) ? MARS_REQ_BAD_TREE : MARS_REQ_BAD_TOKEN);
+    if (g == 0) write_rejected_request<NT>(a, b, (sh_bad & 1) ? MARS_REQ_BAD_TREE : MARS_REQ_BAD_TOKEN, sh_st[0].id1);
     return;
   }
   const int nwords = (N + kWave - 1) / kWave;
