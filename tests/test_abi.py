@@ -175,3 +175,16 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(binding.MarsError):
         binding.lib()
+
+
+def test_source_digest_ignores_comments_and_white_space():
+    """bench.py ties a hardware-counter capture to the kernel's code: rewording a comment or
+    re-indenting must not change the digest, changing a token must."""
+    import bench
+    a = 'int f(int x) { // add one\n  return x + 1;  /* really\n one */ }\nconst char* s = "// kept";\n'
+    b = 'int f(int x) {\n    return x + 1; }\n\n\nconst char* s = "// kept";   // a note\n'
+    c = a.replace("x + 1", "x + 2")
+    assert bench._code_only(a) == bench._code_only(b)
+    assert bench._code_only(a) != bench._code_only(c)
+    assert '"// kept"' in bench._code_only(a)
+    assert len(bench.kernel_source_digest()) == 16
