@@ -70,6 +70,7 @@ SHAPES = [
     dict(B=3, N=40, H=1024, V=257, tree={"kind": "tree", "depth": 6, "max_children": 3}),    # tile of one entry
     dict(B=9, N=43, H=256, V=4096, tree={"kind": "tree", "depth": 5, "max_children": 4}),    # 387 rows: slabs of 128 + ragged slab
     dict(B=2, N=50, H=640, V=70001, tree={"kind": "chain"}),                                 # 100 rows: 137 runs, each from its own slab of the 10 along H
+    dict(B=2, N=20, H=256, V=300007, tree={"kind": "chain"}),                                # a vocabulary of 1172 tiles, the last one ragged
 ]
 
 
