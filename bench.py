@@ -14,11 +14,15 @@ input sets are rotated so that a step never finds its logits in the 256 MB memor
   sweep7    the same with seven thresholds per request (0.84 .. 0.96) from one read of the logits
   margin    mars_margin_stats on the same logits (top-2 statistics per row and their histograms)
   spd       mars_verify on chains of 6 drafts with a dense draft distribution, B = 128, T = 1
+  single_greedy / single_sampling
+            mars_verify on one request (a 60-node tree, V = 151 936, bf16) at T = 0 / at T = 1 with a
+            one-hot draft distribution: the latency of a single pass, issued on one stream
   lmhead    mars_lmhead_verify: greedy verification from the last hidden states (H = 4096) and the
             LM-head weight [151 936, 4096], the logits never written to memory; its roofline object
             is the matrix-core one (bf16 MFMA peak) of the fused kernel
 
-The timed steps are issued round-robin on ``--streams`` HIP streams (default 2), each with its own
+The timed steps are issued round-robin on ``--streams`` HIP streams (default 2; 1 for the
+single-request workloads), each with its own
 workspace and outputs: the library keeps no state and calls with different workspaces may overlap,
 so the latency-bound per-request kernel of one step runs beside the bandwidth-bound row reduction
 of the next, as a server verifying two micro-batches would have it.  ``value`` is the throughput of
@@ -59,6 +63,12 @@ WORKLOADS = {
                                "of z1, z2/z1, p2/p1 (40/50/50 cells)"),
     "spd": dict(cfg=5, what="chains of 6 drafts (N=7), B=128, V=151936, bf16 logits, dense fp32 draft distribution, "
                             "T=1, theta=0.9"),
+    "single_greedy": dict(cfg=1, temperature=0.0, streams=1,
+                          what="configs[1] with T=0: one request, a 60-node tree, V=151936, bf16 logits, theta=0.9 "
+                               "(the latency of a single greedy pass)"),
+    "single_sampling": dict(cfg=1, streams=1,
+                            what="configs[1] with T=1.0 and a one-hot draft distribution: one request, a 60-node "
+                                 "tree, V=151936, bf16 logits, theta=0.9 (the latency of a single sampling pass)"),
     "lmhead": dict(cfg=None, what="greedy verification from hidden states: B=16, 60-node tree per request, H=4096, "
                                   "V=151936, bf16 hidden states and LM-head weight, theta=0.9; logits formed, reduced "
                                   "and dropped inside one kernel"),
@@ -230,7 +240,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="headline")
-    ap.add_argument("--streams", type=int, default=2, help="HIP streams the timed steps alternate over")
+    ap.add_argument("--streams", type=int, default=None,
+                    help="HIP streams the timed steps alternate over (default: 2; 1 for the single-request workloads, "
+                         "whose figure is a latency)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for hardware-counter runs: a few launches of the row reduction on the headline "
@@ -261,6 +273,8 @@ def main() -> int:
     B, N, V = spec["B"], spec["N"], spec["V"]
     rows = B * N
     elt = 2 if spec["dtype"] == "bf16" else 4
+    if "temperature" in WORKLOADS[wl]:
+        spec["temperature"] = WORKLOADS[wl]["temperature"]
     T = spec["temperature"]
     K = len(SWEEP) if wl == "sweep7" else 1
     if wl == "sweep7":
@@ -278,11 +292,11 @@ def main() -> int:
             tok=torch.from_numpy(w.draft_tokens).to(dev),
             par=torch.from_numpy(w.tree_parent).to(dev),
             theta=torch.from_numpy(np.ascontiguousarray(theta)).to(dev),
-            u=torch.from_numpy(w.uniforms).to(dev),
-            q=torch.from_numpy(w.draft_probs).to(dev)))
+            u=None if w.uniforms is None else torch.from_numpy(w.uniforms).to(dev),        # greedy: none drawn
+            q=None if w.draft_probs is None else torch.from_numpy(w.draft_probs).to(dev)))  # None: one-hot
     t_gen = time.perf_counter() - t_gen
 
-    n_streams = max(1, args.streams)
+    n_streams = max(1, args.streams if args.streams is not None else WORKLOADS[wl].get("streams", 2))
     streams = [torch.cuda.Stream() for _ in range(n_streams)]
     wss = [M.alloc_workspace(B, N, V, dev, n_theta=K) for _ in range(n_streams)]
     outs = [M.VerifyOutputs(B, N, dev, n_theta=K, want_commit=(wl == "commit")) for _ in range(n_streams)]
@@ -295,7 +309,7 @@ def main() -> int:
     def step(i, j=0):
         """One pass over input set i with the workspace and outputs of slot j, on the current stream."""
         s = sets[i % N_BUFFERS]
-        if wl in ("headline", "spd"):
+        if wl in ("headline", "spd", "single_greedy", "single_sampling"):
             M.mars_verify(s["logits"], s["tok"], s["par"], s["theta"], T, s["u"], s["q"], outs[j], wss[j])
         elif wl == "margin":
             M.mars_margin_stats(s["logits"], s["theta"], T, MARGIN_RANGES, MARGIN_BINS, margin_rows[j],
@@ -320,12 +334,17 @@ def main() -> int:
         """Wall time of n_steps passes issued round-robin over n_str streams (0: the current stream)."""
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(n_steps):
-            if n_str == 0:
-                step(i)
-            else:
-                with torch.cuda.stream(streams[i % n_str]):
-                    step(i, i % n_str)
+        if n_str == 1:  # (one context for the whole loop: entering one per step costs the host ~6 us)
+            with torch.cuda.stream(streams[0]):
+                for i in range(n_steps):
+                    step(i, 0)
+        else:
+            for i in range(n_steps):
+                if n_str == 0:
+                    step(i)
+                else:
+                    with torch.cuda.stream(streams[i % n_str]):
+                        step(i, i % n_str)
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
@@ -369,7 +388,7 @@ def main() -> int:
     metric = "verify rows/s + achieved HBM GB/s vs peak, B=16 tree-60 V=151936 bf16"
     if wl != "headline":
         metric = f"rows/s + achieved HBM GB/s vs peak, workload '{wl}'"
-    k1_name = "row_reduce_kernel<bf16, 8 per load, %s>" % ("top-2 only" if wl == "margin" else "sampling")
+    k1_name = "row_reduce_kernel<bf16, 8 per load, %s>" % ("top-2 only" if k1_temperature == 0.0 else "sampling")
     result = {
         "metric": metric,
         "value": value,
