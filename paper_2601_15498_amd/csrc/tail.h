@@ -611,7 +611,10 @@ __global__ __launch_bounds__(RESIDENT ? kSamplingThreads : kStreamingThreads) vo
     pending_norm = false;
     have = false;
     applied = 0;
-    // children of cnode, as bit masks over the nodes (increasing node index = increasing bit)
+    // children of cnode, as bit masks over the nodes (increasing node index = increasing bit).
+    // The barrier keeps a wave that has just accepted a child from overwriting the masks of the
+    // previous node while another wave is still reading them.
+    __syncthreads();
     for (int wd = wave; wd < nwords; wd += NW) {
       const int i = wd * kWave + lane;
       const unsigned long long m = __ballot(i < N && i > cnode && sh_par[i] == cnode);
