@@ -57,7 +57,8 @@ enum {
   MARS_ERR_ARG       = -1, /* null required pointer, B/N/V out of range, T < 0 or NaN */
   MARS_ERR_DTYPE     = -2, /* unknown element type */
   MARS_ERR_WORKSPACE = -3, /* workspace missing, misaligned or too small */
-  MARS_ERR_HIP       = -4  /* a kernel launch failed; kernels of the same call launched before it stay enqueued */
+  MARS_ERR_HIP       = -4, /* a kernel launch failed; kernels of the same call launched before it stay enqueued */
+  MARS_ERR_SCRATCH   = -5  /* mars_verify_static: these sizes need more than MARS_STATIC_SCRATCH_BYTES */
 };
 
 /* Per-request status written by the device (data-dependent problems). */
@@ -280,6 +281,36 @@ int mars_verify_ex(const void* logits, int logits_dtype,
                    mars_row_stat* stats, mars_req_diag* diag,
                    void* workspace, size_t workspace_bytes, void* hip_stream,
                    const mars_verify_options* options);
+
+/*
+ * mars_verify_ex for callers that cannot allocate or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  The partial results of the row
+ * reduction, the merged statistics and the exchange words of the sampling-mode walk live in a
+ * device array of MARS_STATIC_SCRATCH_BYTES that is part of the library's code object: every GPU the
+ * library runs on holds its own copy from load until the process ends.  The call allocates
+ * nothing, frees nothing and calls no routine that does; on its first use on a GPU it looks up the
+ * array's device address (once per GPU, with that GPU current) and keeps it.
+ *
+ * Arguments, outputs and errors as for mars_verify_ex (options may be NULL), without workspace and
+ * workspace_bytes.  Sizes whose mars_workspace_bytes_ex(B,N,V,n_theta) exceeds
+ * MARS_STATIC_SCRATCH_BYTES are rejected with MARS_ERR_SCRATCH and nothing is enqueued (the
+ * headline shape, 16 requests of 60 nodes over 151 936 entries, needs 0.7 MB; 256 requests of 26
+ * nodes 1.4 MB).  The kernels are launched on hip_stream, which must belong to the current GPU.
+ * All calls on one GPU share that GPU's array: it keeps the previous call's contents (whatever has
+ * to start at zero is cleared by the call's own first kernel), and calls that overlap on one GPU --
+ * on different streams, or a graph replay beside an eager call -- race on it and give undefined
+ * results.  Calls on one stream, one after the other, are safe.
+ */
+#define MARS_STATIC_SCRATCH_BYTES (8u << 20)
+int mars_verify_static(const void* logits, int logits_dtype,
+                       const int32_t* draft_tokens, const int32_t* tree_parent,
+                       const void* draft_probs, int draft_dtype,
+                       const float* theta, float temperature, const float* uniforms,
+                       int B, int N, int V,
+                       uint8_t* accept_mask, int32_t* accept_len, int32_t* path_idx,
+                       int32_t* bonus_token, uint8_t* decision, int32_t* request_status,
+                       mars_row_stat* stats, mars_req_diag* diag,
+                       void* hip_stream, const mars_verify_options* options);
 
 /* One row of mars_margin_stats: the two largest logits, their ratio fl32(z2/z1) (IEEE result also
  * when z1 <= 0) and the probability ratio P(v2)/P(v1) = exp(-(z1 - z2)/T'), T' as above. */

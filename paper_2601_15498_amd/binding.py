@@ -19,6 +19,8 @@ MARS_MAX_NODES = 1024
 MARS_MAX_THETAS = 64
 MARS_IND_LOGIT_RATIO, MARS_IND_PROB_RATIO, MARS_IND_LOGIT_GAP = 0, 1, 2
 MARS_STAGE_ROWS, MARS_STAGE_REQUESTS = 1, 2
+MARS_STATIC_SCRATCH_BYTES = 8 << 20
+MARS_ERR_SCRATCH = -5
 
 
 class VerifyOptionsStruct(ctypes.Structure):
@@ -64,6 +66,9 @@ def lib():
         L.mars_workspace_bytes_ex.argtypes = [ctypes.c_int] * 4
         L.mars_verify_ex.restype = ctypes.c_int
         L.mars_verify_ex.argtypes = L.mars_verify.argtypes + [ctypes.POINTER(VerifyOptionsStruct)]
+        L.mars_verify_static.restype = ctypes.c_int
+        L.mars_verify_static.argtypes = (L.mars_verify.argtypes[:20] + [ctypes.c_void_p,
+                                                                        ctypes.POINTER(VerifyOptionsStruct)])
         L.mars_margin_stats.restype = ctypes.c_int
         L.mars_margin_stats.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_float,
                                         ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -251,6 +256,41 @@ def mars_verify_ex(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent
                                 _ptr(out.bonus_token), _ptr(out.decision), _ptr(out.request_status),
                                 _ptr(out.stats), _ptr(out.diag), _ptr(workspace), workspace.numel(), _stream(),
                                 ctypes.byref(opt)))
+    return out
+
+
+def mars_verify_static(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: torch.Tensor,
+                       theta: torch.Tensor, temperature: float, uniforms: torch.Tensor = None,
+                       draft_probs: torch.Tensor = None, out: VerifyOutputs = None,
+                       indicator: int = MARS_IND_LOGIT_RATIO, n_theta: int = 1,
+                       want_commit: bool = False, spin_limit: int = 0) -> VerifyOutputs:
+    """mars_verify_ex on the library's own static scratch array (no workspace argument, nothing allocated by
+    the call itself; ``out`` should be given by a caller that must not allocate).  See include/mars.h."""
+    B, N, V = logits.shape
+    dev = logits.device
+    assert logits.is_contiguous()
+    assert draft_tokens.dtype == torch.int32 and draft_tokens.shape == (B, N) and draft_tokens.is_contiguous()
+    assert tree_parent.dtype == torch.int32 and tree_parent.shape == (B, N) and tree_parent.is_contiguous()
+    assert theta.dtype == torch.float32 and theta.numel() == n_theta * B and theta.is_contiguous()
+    if uniforms is not None:
+        assert uniforms.dtype == torch.float32 and uniforms.shape == (B, N + 1) and uniforms.is_contiguous()
+    dcode = 0
+    if draft_probs is not None:
+        assert draft_probs.shape == (B, N, V) and draft_probs.is_contiguous()
+        dcode = _dtype_code(draft_probs)
+    if out is None:
+        out = VerifyOutputs(B, N, dev, n_theta=n_theta, want_commit=want_commit)
+    assert out.n_theta == n_theta
+    opt = VerifyOptionsStruct(int(indicator), int(n_theta), int(spin_limit), 0,
+                              None if out.out_tokens is None else out.out_tokens.data_ptr(),
+                              None if out.out_len is None else out.out_len.data_ptr(),
+                              None if out.keep_rows is None else out.keep_rows.data_ptr(),
+                              None if out.keep_offsets is None else out.keep_offsets.data_ptr())
+    _check(lib().mars_verify_static(_ptr(logits), _dtype_code(logits), _ptr(draft_tokens), _ptr(tree_parent),
+                                    _ptr(draft_probs), dcode, _ptr(theta), float(temperature), _ptr(uniforms),
+                                    B, N, V, _ptr(out.accept_mask), _ptr(out.accept_len), _ptr(out.path_idx),
+                                    _ptr(out.bonus_token), _ptr(out.decision), _ptr(out.request_status),
+                                    _ptr(out.stats), _ptr(out.diag), _stream(), ctypes.byref(opt)))
     return out
 
 

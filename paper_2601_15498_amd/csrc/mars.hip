@@ -4,6 +4,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <mutex>
 
 #include "../../include/mars.h"
 #include "common.h"
@@ -171,6 +172,27 @@ static LmLayout lm_layout(int B, int N, int V, int K) {
   return L;
 }
 
+// Scratch of mars_verify_static: one copy per GPU, held from the moment the library is loaded on it
+// until the process ends.  In host code the array's name is only a handle for the symbol lookup
+// below; kernels are given the device address the lookup returns.
+static __device__ __align__(256) unsigned char scratch[MARS_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on every GPU seen so far
+static std::mutex g_scratch_lock;
+
+// Device address of the current GPU's copy of `scratch` (looked up once per GPU), nullptr on failure.
+static void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+
 static bool lm_sizes_ok(int B, int N, int V, int H, int K) {
   return sizes_ok(B, N, V, K) && H >= kLmBK * kLmDepth && H % (kLmBK * kLmDepth) == 0 && static_cast<long>(B) * N <= (1L << 22);
 }
@@ -188,6 +210,7 @@ const char* mars_status_string(int status) {
     case MARS_ERR_DTYPE: return "unknown element type";
     case MARS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case MARS_ERR_HIP: return "HIP call failed";
+    case MARS_ERR_SCRATCH: return "sizes need more scratch memory than mars_verify_static holds";
     default: return "unknown status";
   }
 }
@@ -358,6 +381,23 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
       hipSuccess)
     return MARS_ERR_HIP;
   return finish();
+}
+
+int mars_verify_static(const void* logits, int logits_dtype, const int32_t* draft_tokens, const int32_t* tree_parent,
+                       const void* draft_probs, int draft_dtype, const float* theta, float temperature,
+                       const float* uniforms, int B, int N, int V, uint8_t* accept_mask, int32_t* accept_len,
+                       int32_t* path_idx, int32_t* bonus_token, uint8_t* decision, int32_t* request_status,
+                       mars_row_stat* stats, mars_req_diag* diag, void* hip_stream,
+                       const mars_verify_options* options) {
+  using namespace mars;
+  const int K = options && options->n_theta != 0 ? options->n_theta : 1;
+  if (!sizes_ok(B, N, V, K)) return MARS_ERR_ARG;
+  if (layout(B, N, V, K).total > static_cast<size_t>(MARS_STATIC_SCRATCH_BYTES)) return MARS_ERR_SCRATCH;
+  void* ws = static_scratch();
+  if (!ws) return MARS_ERR_HIP;
+  return mars_verify_ex(logits, logits_dtype, draft_tokens, tree_parent, draft_probs, draft_dtype, theta, temperature,
+                        uniforms, B, N, V, accept_mask, accept_len, path_idx, bonus_token, decision, request_status,
+                        stats, diag, ws, MARS_STATIC_SCRATCH_BYTES, hip_stream, options);
 }
 
 int mars_margin_stats(const void* logits, int logits_dtype, const float* theta, float temperature, int B, int N, int V,

@@ -29,7 +29,8 @@ def declared_functions():
 def test_header_declares_the_expected_entry_points():
     assert declared_functions() == ["mars_lmhead_verify", "mars_lmhead_workspace_bytes", "mars_margin_stats",
                                     "mars_row_reduce", "mars_row_stats", "mars_status_string",
-                                    "mars_verify", "mars_verify_ex", "mars_version", "mars_workspace_bytes",
+                                    "mars_verify", "mars_verify_ex", "mars_verify_static", "mars_version",
+                                    "mars_workspace_bytes",
                                     "mars_workspace_bytes_ex"]
 
 
@@ -56,7 +57,7 @@ def test_struct_sizes_match_the_binding():
 def test_version_and_status_strings(lib):
     assert lib.mars_version() >= 100
     assert lib.mars_status_string(0) == b"ok"
-    for code in (-1, -2, -3, -4, -99):
+    for code in (-1, -2, -3, -4, -5, -99):
         assert len(lib.mars_status_string(code)) > 0
 
 
