@@ -66,8 +66,8 @@ enum {
   MARS_REQ_OK        = 0,
   MARS_REQ_BAD_TREE  = 1, /* parent[0] != -1, or parent[i] not in [0, i) for i >= 1 */
   MARS_REQ_BAD_TOKEN = 2, /* draft token of a node i >= 1 outside [0, V) */
-  MARS_REQ_TIMEOUT   = 3  /* sampling mode: the work-groups sharing this request did not all arrive
-                             (the GPU was not free to run them together); outputs are undefined */
+  MARS_REQ_TIMEOUT   = 3  /* not produced any more (a work-group no longer gives up on its partners: it works
+                             out their share itself); the value is kept so that old callers still compile */
 };
 
 /* decision[b,i] codes (Sec. 3.4 bullets; code 3 is Eq. 1's stochastic accept). */
@@ -183,8 +183,8 @@ int mars_row_stats(const void* logits, int logits_dtype, const float* theta,
  *   bonus_token   device out, [B] int32.
  *   decision      device out, optional (NULL ok), [B,N] uint8 MARS_DEC_* codes.
  *   request_status device out, optional (NULL ok), [B] int32 MARS_REQ_* codes.  A
- *                 request with a non-zero status gets accept_len = 0, an empty path
- *                 and bonus_token = v(1) of its root row.
+ *                 request with a non-zero status (malformed tree, token out of range) gets
+ *                 accept_len = 0, an empty path and bonus_token = v(1) of its root row.
  *   stats         device out, optional (NULL ok), [B*N] row statistics.
  *   diag          device out, optional (NULL ok), [B]; in greedy mode only last_node is set.
  *   workspace     device, >= mars_workspace_bytes(B,N,V), 256-byte aligned.
@@ -199,9 +199,9 @@ int mars_row_stats(const void* logits, int logits_dtype, const float* theta,
  *
  * Returns MARS_OK or a negative code; on error nothing is enqueued.
  * Calls that share a workspace must not overlap.  Calls with workspaces (and outputs) of their
- * own may run side by side on different streams: the library keeps no state, and the
+ * own may run side by side on any number of streams: the library keeps no state, the
  * latency-bound per-request kernel of one call then runs beside the bandwidth-bound row
- * reduction of another.
+ * reduction of another, and no work-group of a call waits for another one to be resident.
  */
 int mars_verify(const void* logits, int logits_dtype,
                 const int32_t* draft_tokens, const int32_t* tree_parent,
@@ -223,19 +223,21 @@ int mars_verify(const void* logits, int logits_dtype,
  *                 reduction runs once, and the per-request part runs for every (k, b) on the same
  *                 inputs; EVERY output of mars_verify gains a leading axis of length K
  *                 (accept_mask [K,B,N], accept_len [K,B], ..., stats [K,B*N], diag [K,B]).
- *   spin_limit    sampling mode: polls a work-group waits for a partner's partial sum before it
- *                 flags the request MARS_REQ_TIMEOUT and carries on (every wait in the library is
- *                 bounded).  0 = the default, on the order of a second.  Only of interest to
- *                 callers that share the GPU with other work, and to tests of that path.
+ *   spin_limit    sampling mode: the work-groups that share a request exchange partial sums.  This is
+ *                 the number of polls (about a microsecond each) a work-group gives a partner before it
+ *                 stops waiting and works out the partner's sum itself -- same bits, so the outputs
+ *                 do not depend on it; no work-group ever depends on another one being resident.
+ *                 0 = the default (256).  Only of interest to callers that share the GPU with other
+ *                 work, and to tests of that path (1 = never wait).
  *   stages        which part of the pass the call enqueues: 0 or MARS_STAGE_ROWS | MARS_STAGE_REQUESTS = all of
  *                 it; MARS_STAGE_ROWS = the row reduction only (it also clears what the second part
  *                 accumulates into); MARS_STAGE_REQUESTS = the per-request part only, on a workspace the
  *                 first part has filled (same arguments in both calls).  Splitting a pass lets a caller
- *                 that overlaps passes on several streams put its own events between the parts: in
- *                 sampling mode the work-groups of a request wait for each other and the per-request part
- *                 of one pass holds up to one work-group per compute unit, so the per-request parts of
- *                 overlapping passes should follow one another (an event recorded after one, waited for
- *                 before the next) while row reductions may run beside them freely.
+ *                 that overlaps passes on several streams put its own events between the parts: the
+ *                 per-request part of a sampling-mode pass holds up to one work-group per compute unit
+ *                 and is quickest when all of them are resident together, so the per-request parts of
+ *                 overlapping passes are best run one after the other while row reductions run beside
+ *                 them freely.
  *   out_tokens    device out, optional, [K,B,N] int32: the committed sequence V_out of Alg. 1 -- the
  *                 tokens of the accepted nodes in path order, then the correction / bonus token,
  *                 then -1.

@@ -19,6 +19,7 @@ constexpr int kMinTargetItems = 128;    // ... and on a small one
 constexpr int kItemElemsLog2 = 16;      // in between: about one work-group per 65 536 elements
 constexpr int kMinSplitElems = 8192;    // no split shorter than this
 constexpr size_t kAlign = 256;
+constexpr int kDefaultSpinLimit = 256;  // polls before a work-group stops waiting for a partner's sum
 
 static size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -45,10 +46,22 @@ struct Layout {
 };
 
 // Work-groups per request in the sampling tail: enough to spread a request's row passes over
-// the chip when there are few requests, never more than one work-group per compute unit in
-// total (they wait for each other, so all of them must be resident), and every slice at least
-// 4096 vocabulary entries long.
+// the chip when there are few requests, not more than one work-group per compute unit in
+// total (they exchange sums, and that is quick only while all of them are resident), and every
+// slice at least 4096 vocabulary entries long.  The workspace is laid out for the compute units
+// of an MI355X; a GPU with fewer gets fewer work-groups per request at launch (below).
 constexpr int kComputeUnits = 256;
+static int compute_units() {  // of the current GPU, asked once
+  static int cached = 0;
+  if (cached <= 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      return kComputeUnits;
+    cached = n;
+  }
+  return cached;
+}
 static int choose_groups(int B, int V) {
   int G = kComputeUnits / B;
   const int cap = V / 4096;
@@ -335,9 +348,14 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
   a.theta = theta; a.u = uniforms; a.partials = partials;
   a.stats = stats;
   a.stats_ws = reinterpret_cast<mars_row_stat*>(ws + L.stats_off);
-  a.G = sampling ? L.G : 1;
-  // by default on the order of a second of polling before a request gives up on its partners
-  a.spin_limit = spin_limit > 0 ? spin_limit : 1 << 20;
+  int groups = L.G;
+  if (static_cast<long>(K) * B * groups > compute_units()) {
+    groups = compute_units() / (K * B);
+    if (groups < 1) groups = 1;
+  }
+  a.G = sampling ? groups : 1;
+  // polls (about a microsecond each) a work-group gives a partner before it works out the partner's sum itself
+  a.spin_limit = spin_limit > 0 ? spin_limit : kDefaultSpinLimit;
   a.xslots = clr.xslots;
   a.mask = accept_mask; a.len = accept_len; a.path = path_idx; a.bonus = bonus_token;
   a.dec = decision; a.status = request_status; a.diag = diag;
@@ -364,18 +382,17 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
   const bool resident = slice8 <= kResident * kSamplingThreads;
   const bool qbf = dense && draft_dtype == MARS_BF16;
   const void* kernel;
-#define MARS_PICK(TT, QQ) (resident ? reinterpret_cast<const void*>(&tail_sampling_kernel<TT, QQ, true>) \
-                                    : reinterpret_cast<const void*>(&tail_sampling_kernel<TT, QQ, false>))
+#define MARS_PICK(TT, QQ) (resident ? reinterpret_cast<const void*>(&tail_sampling_resident_kernel<TT, QQ>) \
+                                    : reinterpret_cast<const void*>(&tail_sampling_streamed_kernel<TT, QQ>))
   if (logits_dtype == MARS_BF16) kernel = qbf ? MARS_PICK(bf16_t, bf16_t) : MARS_PICK(bf16_t, float);
   else kernel = qbf ? MARS_PICK(float, bf16_t) : MARS_PICK(float, float);
 #undef MARS_PICK
   void* params[] = {&a};
-  // With G > 1 the work-groups of a request wait for each other.  The grid never exceeds one
-  // work-group per compute unit, so on a device that is free to run it (the row reduction before
-  // it on the same stream has finished by then) every work-group is resident from the start.
-  // The waits are bounded: should foreign work keep part of the grid from being scheduled, the
-  // affected requests end with MARS_REQ_TIMEOUT instead of hanging.  (A cooperative launch
-  // would have the runtime check residency, at the price of ~20 us per call on this stack.)
+  // With G > 1 the work-groups of a request exchange sums.  The grid never exceeds one work-group
+  // per compute unit, so on a GPU that is free to run it all of them are resident together and the
+  // exchanges take a couple of microseconds; when other work keeps some of them waiting for a
+  // compute unit, those that run work out the missing sums themselves (tail.h: exchange_sum) --
+  // slower, same bits, and no work-group ever depends on another one being there.
   if (hipLaunchKernel(kernel, dim3(static_cast<unsigned int>(K * B) * a.G), dim3(resident ? kSamplingThreads : kStreamingThreads), params, 0,
                       stream) !=
       hipSuccess)

@@ -20,14 +20,8 @@
 
 namespace mars {
 
-#ifndef MARS_ROW_THREADS
-#define MARS_ROW_THREADS 512
-#endif
-#ifndef MARS_ROW_UNROLL
-#define MARS_ROW_UNROLL 2
-#endif
-constexpr int kRowThreads = MARS_ROW_THREADS;  // 8 waves per work-group (512 x 2 measured best of {128..1024} x {1,2,4,8})
-constexpr int kUnroll = MARS_ROW_UNROLL;       // 16-byte loads per lane per batch
+constexpr int kRowThreads = 512;  // 8 waves per work-group (512 x 2 measured best of {128..1024} x {1,2,4,8})
+constexpr int kUnroll = 2;        // 16-byte loads per lane per batch
 constexpr float kRescaleLog2 = 24.0f;  // move the sum-exp reference when the max rises by 2^24
 
 // Insert the elements >= cut of one vector into the running key pair (k1 >= k2).  Only a

@@ -18,6 +18,7 @@ constexpr int kGreedyThreads = 1024;  // 64 rows merged at a time
 constexpr int kSamplingThreads = 512;    // sampling tail whose slices stay in registers
 constexpr int kStreamingThreads = 1024;  // sampling tail that streams its slices: more loads in flight per compute unit
 constexpr int kMaxTiles = 512;  // CDF tiles kept in LDS for the final draw
+constexpr int kMaxGroupsPerRequest = 32;   // work-groups that may share one request
 
 struct TailArgs {
   const void* logits;
@@ -47,7 +48,7 @@ struct TailArgs {
   float c;               // log2(e) / T, 0 in greedy mode
   // sampling mode: G work-groups share one request and exchange partial sums
   int G;
-  int spin_limit;        // polls before an exchange gives up
+  int spin_limit;        // polls a work-group gives a partner before it works out the partner's sum itself
   unsigned long long* xslots;  // [B][N+2][G][2] tagged exchange words, cleared by the row reduction
 };
 
@@ -265,22 +266,35 @@ __device__ __forceinline__ double block_sum(double v, double* sh) {
 // 2*G words, cleared by the row reduction of the same call.  A work-group publishes its value as
 // two floats (head and tail of the double), each packed with a non-zero tag into one 64-bit
 // word, so that a single store both delivers the data and signals arrival; the partners poll
-// the words directly.  The wait is bounded: if a partner does not arrive within `spin_limit`
-// polls the request is flagged and the kernel carries on to its end with what it has.
+// the words directly.
+//
+// No work-group depends on another one being there.  A partner whose words have not arrived
+// after `spin_limit` polls (it may not have been given a compute unit yet: the GPU is shared with
+// other kernels, other streams, other calls of this library) is not waited for any longer: the
+// work-group goes over that partner's slice itself, with the partner's own assignment of elements
+// to threads and order of additions, so that it obtains the very bits the partner will publish,
+// and carries on.  Whatever the placement of the work-groups, every one of them finishes, and
+// all agree.  The exchange therefore comes in three steps, and the caller's pass over a slice is
+// written once, inside a loop over "whose slice": its own first, then those of the missing partners.
+//   exchange_begin  publish `mine`, poll the partners; returns the set of those that did not arrive
+//   exchange_fill   the value worked out here for a missing partner
+//   exchange_end    the sum, in work-group order
 __device__ __forceinline__ unsigned long long pack_tagged(float v) {
   return (1ull << 32) | static_cast<unsigned long long>(__float_as_uint(v));
 }
 template <int NT>
-__device__ double exchange_sum(const TailArgs& a, int b, int g, int idx, double mine, double* sh_part,
-                               int* sh_flag) {
+__device__ __forceinline__ unsigned int exchange_begin(const TailArgs& a, int b, int g, int idx, double mine,
+                                                       double* sh_part, unsigned int* sh_missing) {
   const int G = a.G;
-  if (G == 1) { sh_part[0] = mine; return mine; }
+  if (G == 1) { sh_part[0] = mine; return 0u; }
+  static_assert(2 * kMaxGroupsPerRequest <= kWave, "one wave polls every word of an exchange");
   unsigned long long* cell = a.xslots + (static_cast<size_t>(b) * (a.N + 2) + idx) * (2 * G);
   if (threadIdx.x == 0) {
     const float hi = static_cast<float>(mine);
     const float lo = static_cast<float>(mine - static_cast<double>(hi));
     __hip_atomic_store(&cell[2 * g], pack_tagged(hi), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(&cell[2 * g + 1], pack_tagged(lo), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *sh_missing = 0u;
   }
   if (threadIdx.x < 2 * G) {
     // One wave polls all 2*G words at once: lane 2i the head of work-group i's value, lane 2i+1 its tail.
@@ -289,7 +303,7 @@ __device__ double exchange_sum(const TailArgs& a, int b, int g, int idx, double 
     for (;;) {
       w = __hip_atomic_load(&cell[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if ((w >> 32) != 0ull) break;
-      if (++spins > a.spin_limit) { *sh_flag = 1; break; }
+      if (++spins > a.spin_limit) { atomicOr(sh_missing, 1u << (threadIdx.x >> 1)); break; }
       __builtin_amdgcn_s_sleep(1);
     }
     double v = static_cast<double>(__uint_as_float(static_cast<unsigned int>(w)));
@@ -297,8 +311,23 @@ __device__ double exchange_sum(const TailArgs& a, int b, int g, int idx, double 
     if ((threadIdx.x & 1) == 0) sh_part[threadIdx.x >> 1] = v;
   }
   __syncthreads();
+  // (written again only behind the barriers of exchange_end; the same in every lane, and said so: what
+  // is derived from it -- whose slice comes next, its bounds -- then lives in scalar registers)
+  return static_cast<unsigned int>(__builtin_amdgcn_readfirstlane(static_cast<int>(*sh_missing)));
+}
+// (a value worked out here goes through the same two floats as one that travelled)
+__device__ __forceinline__ void exchange_fill(double* sh_part, int i, double v) {
+  if (threadIdx.x == 0) {
+    const float hi = static_cast<float>(v);
+    const float lo = static_cast<float>(v - static_cast<double>(hi));
+    sh_part[i] = static_cast<double>(hi) + static_cast<double>(lo);
+  }
+}
+__device__ __forceinline__ double exchange_end(const TailArgs& a, const double* sh_part) {
+  if (a.G == 1) return sh_part[0];
+  __syncthreads();
   double t = 0.0;
-  for (int i = 0; i < G; ++i) t += sh_part[i];
+  for (int i = 0; i < a.G; ++i) t += sh_part[i];
   __syncthreads();  // sh_part may be rewritten by the next exchange
   return t;
 }
@@ -333,7 +362,7 @@ constexpr int kPassBatch = 4;  // groups whose loads a thread issues before it s
 // q_k dense, or one-hot at token x.  The loads of kPassBatch groups are issued together so
 // that a pass costs about one memory round trip per batch, not one per group.
 template <typename T, typename TQ, int NT>
-__device__ double residual_mass_slice(const RowView<T, TQ>& rv, int g_begin, int g_end, int x) {
+__device__ __forceinline__ double residual_mass_slice(const RowView<T, TQ>& rv, int g_begin, int g_end, int x) {
   double part = 0.0;
   for (int base = g_begin + static_cast<int>(threadIdx.x); base < g_end; base += kPassBatch * NT) {
     float z[kPassBatch][8], q[kPassBatch][8];
@@ -431,13 +460,61 @@ __device__ __forceinline__ void tile_find(const double* sh_tile, int n, int lane
   cum = front;
 }
 
-constexpr int kMaxGroupsPerRequest = 32;   // work-groups that may share one request
+// A slice that is resident in a partner's registers, gone over from memory here because the partner has
+// not arrived (see exchange_begin).  A rarely taken path: one group of eight at a time, so that it adds next
+// to nothing to the registers of the walk around it; groups go to threads, and sums are formed, as in the
+// owner's resident form.  (The streamed form of the tail needs no such twin: its own pass reads memory.)
+template <typename T, typename TQ, int NT>
+__device__ __forceinline__ double resident_mass_from_memory(const RowView<T, TQ>& rv, int gb, int ge, int x) {
+  double part = 0.0;
+#pragma unroll 1
+  for (int gi = gb + static_cast<int>(threadIdx.x); gi < ge; gi += NT) {
+    float z[8], q[8];
+    rv.load(gi, z, q);
+    float acc = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float qk = rv.qrow ? q[e] : (gi * 8 + e == x ? 1.0f : 0.0f);
+      acc += fmaxf(rv.f(z, q, gi, e) - qk, 0.0f);
+    }
+    part += static_cast<double>(acc);
+  }
+  return part;
+}
+// Tile sums (a tile = a step of 64 groups, the steps dealt out to the waves in turn); returns their number.
+template <typename T, typename TQ, int NT, int kRes>
+__device__ __forceinline__ int resident_tiles_from_memory(const RowView<T, TQ>& rv, int gb, int ge, double* out) {
+  constexpr int NW = NT / kWave;
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int nst = (ge - gb + kWave - 1) / kWave;
+#pragma unroll 1
+  for (int i = 0; i < kRes; ++i) {
+    const int s = i * NW + wave;
+    if (s < nst) {  // wave-uniform
+      const int gi = gb + i * NT + tid;
+      float gs = 0.0f;
+      if (gi < ge) {
+        float z[8], q[8], f[8];
+        rv.load(gi, z, q);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = rv.f(z, q, gi, e);
+        gs = ((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7]));
+      }
+      const double t = wave_sum(static_cast<double>(gs));
+      if (lane == 0) out[s] = t;
+    }
+  }
+  return nst;
+}
+
 constexpr float kClosedFormMinNorm = 0.1f; // one-hot residual: Z = 1 - f(x) is used when at least this
 constexpr int kResident = 3;               // groups of eight elements a thread can keep in registers
 
 // RESIDENT: every slice is at most kResident groups per thread (decided by the host from G and V).
+// (At most 184 registers: a work-group of the row reduction of another call -- two waves per SIMD at 72 -- then
+// still fits on a compute unit beside a resident tail's two at 184, and calls on two streams overlap.)
 template <typename T, typename TQ, bool RESIDENT>
-__global__ __launch_bounds__(RESIDENT ? kSamplingThreads : kStreamingThreads) void tail_sampling_kernel(TailArgs a) {
+__device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   constexpr int NT = RESIDENT ? kSamplingThreads : kStreamingThreads;
   constexpr int NW = NT / kWave;
   __shared__ int16_t sh_par[MARS_MAX_NODES];     // parent of every node
@@ -452,7 +529,8 @@ __global__ __launch_bounds__(RESIDENT ? kSamplingThreads : kStreamingThreads) vo
   __shared__ double sh_part[kMaxGroupsPerRequest];
   __shared__ double sh_tile[kMaxTiles];
   __shared__ float sh_u[MARS_MAX_NODES + 1];     // the request's uniforms
-  __shared__ int sh_flag;                        // exchange timed out
+  __shared__ double sh_tile2[kMaxTiles];         // tile sums of a partner's slice, when they have to be worked out here
+  __shared__ unsigned int sh_missing;            // partners of the current exchange that have not arrived
   __shared__ int sh_bad;                         // validation bits of the request
 
   const int G = a.G;
@@ -463,7 +541,7 @@ __global__ __launch_bounds__(RESIDENT ? kSamplingThreads : kStreamingThreads) vo
   const size_t rd = static_cast<size_t>(bd) * N;
   const int tid = threadIdx.x;
   const int wave = tid / kWave, lane = tid % kWave;
-  if (tid == 0) { sh_flag = 0; sh_bad = 0; }
+  if (tid == 0) sh_bad = 0;
   __syncthreads();
 
   const T* __restrict__ zall = static_cast<const T*>(a.logits) + rd * static_cast<size_t>(V);
@@ -672,9 +750,13 @@ __global__ __launch_bounds__(RESIDENT ? kSamplingThreads : kStreamingThreads) vo
         pending_norm = true;
         inv = 1.0f;
       } else {
-        double part = 0.0;
+        // This work-group's slice first, then (rarely) those of partners that have not arrived.  The
+        // streamed form reads memory either way and runs one loop over "whose slice"; the resident form has
+        // its own slice in registers and a lean pass over memory for the others, kept out of the way
+        // behind the exchange (both forms are short of registers in different places).
         if (resident) {
           refresh_resident();
+          double part = 0.0;
 #pragma unroll
           for (int i = 0; i < kResident; ++i) {
             const int gi = g_begin + i * NT + tid;
@@ -686,11 +768,34 @@ __global__ __launch_bounds__(RESIDENT ? kSamplingThreads : kStreamingThreads) vo
             }
             part += static_cast<double>(acc);
           }
+          part = block_sum<NT>(part, sh_red);
+          unsigned int missing = exchange_begin<NT>(a, b, g, nexch++, part, sh_part, &sh_missing);
+          while (missing != 0u) {
+            const int who = __ffs(static_cast<int>(missing)) - 1;
+            missing &= missing - 1u;
+            const int gb = min(ngroups, who * slice), ge = min(ngroups, gb + slice);
+            const double theirs = block_sum<NT>(resident_mass_from_memory<T, TQ, NT>(rv, gb, ge, x), sh_red);
+            exchange_fill(sh_part, who, theirs);
+            __syncthreads();  // (sh_red is free again)
+          }
         } else {
-          part = residual_mass_slice<T, TQ, NT>(rv, g_begin, g_end, x);
+          int who = g;
+          unsigned int missing = 0u;
+          for (;;) {
+            const int gb = min(ngroups, who * slice), ge = min(ngroups, gb + slice);
+            const double part = block_sum<NT>(residual_mass_slice<T, TQ, NT>(rv, gb, ge, x), sh_red);
+            if (who == g) {
+              missing = exchange_begin<NT>(a, b, g, nexch++, part, sh_part, &sh_missing);
+            } else {
+              exchange_fill(sh_part, who, part);
+              __syncthreads();  // (sh_red is free again)
+            }
+            if (missing == 0u) break;
+            who = __ffs(static_cast<int>(missing)) - 1;
+            missing &= missing - 1u;
+          }
         }
-        part = block_sum<NT>(part, sh_red);
-        const double Z = exchange_sum<NT>(a, b, g, nexch++, part, sh_part, &sh_flag);
+        const double Z = exchange_end(a, sh_part);
         last_norm = static_cast<float>(Z);
         inv = Z > 0.0 ? static_cast<float>(1.0 / Z) : 0.0f;  // 0: f is left as it is
       }
@@ -732,6 +837,8 @@ __global__ __launch_bounds__(RESIDENT ? kSamplingThreads : kStreamingThreads) vo
   double total = 0.0, before = 0.0;
   int owner = 0;
   for (int attempt = 0; attempt < 2; ++attempt) {
+    // This work-group's slice first (tile sums into sh_tile, which the search below reads), then (rarely)
+    // those of partners that have not arrived (into sh_tile2); the two forms as above.
     if (resident) {
       refresh_resident();
 #pragma unroll
@@ -744,35 +851,68 @@ __global__ __launch_bounds__(RESIDENT ? kSamplingThreads : kStreamingThreads) vo
           if (lane == 0) sh_tile[s] = t;
         }
       }
+      __syncthreads();
+      // slice total = sum of its tiles, taken by the same prefix scheme the search below uses
+      unsigned int missing = exchange_begin<NT>(a, b, g, N + attempt, tile_total(sh_tile, nsteps, lane), sh_part, &sh_missing);
+      while (missing != 0u) {
+        const int who = __ffs(static_cast<int>(missing)) - 1;
+        missing &= missing - 1u;
+        const int gb = min(ngroups, who * slice), ge = min(ngroups, gb + slice);
+        const int nt = resident_tiles_from_memory<T, TQ, NT, kResident>(rv, gb, ge, sh_tile2);
+        __syncthreads();
+        exchange_fill(sh_part, who, tile_total(sh_tile2, nt, lane));
+        __syncthreads();  // (sh_tile2 may be filled again)
+      }
     } else {
-      // tile sums of this work-group's slice, kPassBatch steps of loads in flight at a time
-      double acc = 0.0;
-      for (int s0 = 0; s0 < steps_per_wave; s0 += kPassBatch) {
-        float z[kPassBatch][8], q[kPassBatch][8];
+      int who = g;
+      unsigned int missing = 0u;
+      for (;;) {
+        const int gb = min(ngroups, who * slice), ge = min(ngroups, gb + slice);
+        double* tiles = who == g ? sh_tile : sh_tile2;
+        // tile sums of a streamed slice, kPassBatch steps of loads in flight at a time
+        const int spw = (((ge - gb + kWave - 1) / kWave) + NW - 1) / NW;  // steps per wave of this slice
+        const int rp = max(1, (spw * NW + kMaxTiles - 1) / kMaxTiles);
+        const int tpw = (spw + rp - 1) / rp;
+        auto group_at = [&](int sw) {  // group of this lane in step sw of its wave, -1 = none
+          const int gi = gb + (wave * spw + sw) * kWave + lane;
+          return (sw < spw && gi < ge) ? gi : -1;
+        };
+        double acc = 0.0;
+        for (int s0 = 0; s0 < spw; s0 += kPassBatch) {
+          float z[kPassBatch][8], q[kPassBatch][8];
 #pragma unroll
-        for (int i = 0; i < kPassBatch; ++i) {
-          const int gi = step_group(wave, s0 + i);
-          if (gi >= 0) rv.load(gi, z[i], q[i]);
-        }
+          for (int i = 0; i < kPassBatch; ++i) {
+            const int gi = group_at(s0 + i);
+            if (gi >= 0) rv.load(gi, z[i], q[i]);
+          }
 #pragma unroll
-        for (int i = 0; i < kPassBatch; ++i) {
-          const int sw = s0 + i;
-          if (sw < steps_per_wave) {
-            const int gi = step_group(wave, sw);
-            if (gi >= 0) { float f[8]; acc += static_cast<double>(group_sum(z[i], q[i], gi, f)); }
-            if ((sw + 1) % rep == 0 || sw + 1 == steps_per_wave) {
-              const double t = wave_sum(acc);
-              if (lane == 0) sh_tile[wave * tiles_per_wave + sw / rep] = t;
-              acc = 0.0;
+          for (int i = 0; i < kPassBatch; ++i) {
+            const int sw = s0 + i;
+            if (sw < spw) {
+              const int gi = group_at(sw);
+              if (gi >= 0) { float f[8]; acc += static_cast<double>(group_sum(z[i], q[i], gi, f)); }
+              if ((sw + 1) % rp == 0 || sw + 1 == spw) {
+                const double t = wave_sum(acc);
+                if (lane == 0) tiles[wave * tpw + sw / rp] = t;
+                acc = 0.0;
+              }
             }
           }
         }
+        __syncthreads();
+        const double slice_total = tile_total(tiles, tpw * NW, lane);
+        if (who == g) {
+          missing = exchange_begin<NT>(a, b, g, N + attempt, slice_total, sh_part, &sh_missing);
+        } else {
+          exchange_fill(sh_part, who, slice_total);
+          __syncthreads();  // (sh_tile2 may be filled again)
+        }
+        if (missing == 0u) break;
+        who = __ffs(static_cast<int>(missing)) - 1;
+        missing &= missing - 1u;
       }
     }
-    __syncthreads();
-    // slice total = sum of its tiles, taken by the same prefix scheme the search below uses
-    const double wg_total = tile_total(sh_tile, ntiles, lane);
-    total = exchange_sum<NT>(a, b, g, N + attempt, wg_total, sh_part, &sh_flag);
+    total = exchange_end(a, sh_part);
     // Which work-group's slice holds the target?  The last one with mass if rounding leaves none.
     const double target = static_cast<double>(u[N]) * total;
     before = 0.0;
@@ -806,10 +946,7 @@ __global__ __launch_bounds__(RESIDENT ? kSamplingThreads : kStreamingThreads) vo
   if (pending_norm) last_norm = static_cast<float>(total);
   const double target = static_cast<double>(u[N]) * total;
   if (g == 0 && tid == 0) a.len[b] = plen;
-  // The request's status was cleared to MARS_REQ_OK by the row reduction of this call.  Any
-  // work-group that gave up on a partner marks the request: its own view of the sums, and with
-  // it whatever it wrote, may be off even if the other work-groups saw every value.
-  if (tid == 0 && a.status && sh_flag) atomicMax(&a.status[b], static_cast<int32_t>(MARS_REQ_TIMEOUT));
+  // (The request's status was set to MARS_REQ_OK by the row reduction of this call.)
   // V_out (Alg. 1): the accepted drafts were written as they were accepted; the first work-group
   // pads behind the slot of the final token, which the work-group that draws it fills in.  (No
   // address is written by two work-groups.)
@@ -924,6 +1061,15 @@ __global__ __launch_bounds__(RESIDENT ? kSamplingThreads : kStreamingThreads) vo
       a.diag[b] = dg;
     }
   }
+}
+
+template <typename T, typename TQ>
+__global__ __launch_bounds__(kSamplingThreads) void tail_sampling_resident_kernel(TailArgs a) {
+  tail_sampling_body<T, TQ, true>(a);
+}
+template <typename T, typename TQ>
+__global__ __launch_bounds__(kStreamingThreads) void tail_sampling_streamed_kernel(TailArgs a) {
+  tail_sampling_body<T, TQ, false>(a);
 }
 
 // ---------------------------------------------------------------- cache rows that stay
