@@ -85,9 +85,21 @@ typedef struct mars_ref_diag {
   double  min_norm;           /* smallest residual normaliser Z met (inf if none) */
   int32_t residual_passes;
   int32_t last_node;
+  int32_t small_norm_plen;    /* drafts accepted so far when the first normaliser below the floor (see
+                                 mars_ref_set_norm_floor) was met, -1 if none: what the walk decided up to
+                                 there does not depend on that normaliser */
+  int32_t small_norm_node;    /* the node whose children were being tried then, -1 if none */
 } mars_ref_diag;
 
 static int g_threads = 1;
+/* A residual normaliser below this is reported in small_norm_plen / small_norm_node.  It changes no
+   result: it only tells a test from where on an fp32 implementation may legitimately differ (Z is a
+   difference of probability masses of order 1, so its relative error grows like 1/Z). */
+static double g_norm_floor = 2e-2;
+
+void mars_ref_set_norm_floor(double z) { g_norm_floor = z; }
+
+double mars_ref_get_norm_floor(void) { return g_norm_floor; }
 
 void mars_ref_set_threads(int n) { g_threads = n < 1 ? 1 : n; }
 
@@ -228,7 +240,7 @@ static void verify_sampling(const void* logits, int ldt, size_t req_base, int V,
   mask[0] = 1;
   int c = 0, plen = 0;
   double min_acc = INFINITY, min_norm = INFINITY, lastZ = 0.0;
-  int passes = 0;
+  int passes = 0, small_plen = -1, small_node = -1;
   for (;;) {
     /* f = softmax(z_c / T), Eq. 3 */
     size_t rb = req_base + (size_t)c * (size_t)V;
@@ -267,6 +279,7 @@ static void verify_sampling(const void* logits, int ldt, size_t req_base, int V,
       }
       ++passes; lastZ = Z;
       if (Z < min_norm) min_norm = Z;
+      if (Z < g_norm_floor && small_plen < 0) { small_plen = plen; small_node = c; }
       /* Z == 0 cannot follow a rejection in exact arithmetic (it needs f <= q everywhere,
          hence f == q and acceptance probability 1); f is left as it is then. */
       if (Z > 0.0)
@@ -309,6 +322,8 @@ static void verify_sampling(const void* logits, int ldt, size_t req_base, int V,
     dg->min_norm = min_norm;
     dg->residual_passes = passes;
     dg->last_node = c;
+    dg->small_norm_plen = small_plen;
+    dg->small_norm_node = small_node;
   }
   free(f);
 }
@@ -347,6 +362,7 @@ int mars_ref_verify_ex(const void* logits, int logits_dtype,
     if (dg) {
       memset(dg, 0, sizeof *dg);
       dg->min_accept_margin = INFINITY; dg->min_cdf_margin = INFINITY; dg->min_norm = INFINITY;
+      dg->small_norm_plen = -1; dg->small_norm_node = -1;
     }
     int s = request_status(tok, par, N, V);
     if (req_status) req_status[b] = s;

@@ -23,7 +23,8 @@ MARGIN_ROW_DTYPE = np.dtype([("z1", "<f8"), ("z2", "<f8"), ("ratio", "<f8"), ("p
 IND_LOGIT_RATIO, IND_PROB_RATIO, IND_LOGIT_GAP = 0, 1, 2
 DIAG_DTYPE = np.dtype([("bonus_prob", "<f8"), ("last_residual_norm", "<f8"),
                        ("min_accept_margin", "<f8"), ("min_cdf_margin", "<f8"), ("min_norm", "<f8"),
-                       ("residual_passes", "<i4"), ("last_node", "<i4")], align=True)
+                       ("residual_passes", "<i4"), ("last_node", "<i4"),
+                       ("small_norm_plen", "<i4"), ("small_norm_node", "<i4")], align=True)
 
 
 def lib():
@@ -41,6 +42,17 @@ def lib():
         assert L.mars_ref_sizeof_diag() == DIAG_DTYPE.itemsize
         _LIB = L
     return _LIB
+
+
+def set_norm_floor(z: float) -> None:
+    """Residual normalisers below ``z`` are reported in diag's small_norm_plen / small_norm_node (no result changes)."""
+    lib().mars_ref_set_norm_floor(ctypes.c_double(float(z)))
+
+
+def get_norm_floor() -> float:
+    L = lib()
+    L.mars_ref_get_norm_floor.restype = ctypes.c_double
+    return float(L.mars_ref_get_norm_floor())
 
 
 def set_threads(n: int) -> None:

@@ -18,7 +18,10 @@ oracle reports it) is below ``guard``:
   about 1e-2 that would come within reach of the guard band.
 
 The path may change after a re-draw, so the oracle is run again until every
-request is clean.  Returns the oracle's output for the final uniforms.
+request is clean.  Returns the oracle's output for the final uniforms.  A request
+that meets a small normaliser whatever is drawn can be kept and flagged instead
+(``allow_small_norm``): what its walk decided before that normaliser is still
+well posed, and the oracle says where that was.
 """
 import numpy as np
 
@@ -31,7 +34,7 @@ def _sub(a, idx):
 
 def screen_uniforms(w, guard: float = 1e-4, min_norm: float = 2e-2, max_rounds: int = 200,
                     seed: int = 987654321, cdf_guard: float = None, indicator: int = 0, thetas=None,
-                    drop_unscreenable: bool = False):
+                    allow_small_norm: bool = False, norm_rounds: int = 40):
     """``w`` is a workload object with numpy fields (logits, draft_tokens, tree_parent, theta,
     temperature, uniforms, draft_probs); ``w.uniforms`` is updated in place.
 
@@ -39,12 +42,17 @@ def screen_uniforms(w, guard: float = 1e-4, min_norm: float = 2e-2, max_rounds: 
     request, so a request is re-drawn until all K of them are clean; the outputs then carry a
     leading axis of length K.
 
-    Some requests cannot be screened whatever is drawn (a peaked distribution whose residual mass stays
-    below ``min_norm`` on every path that is at all likely).  With ``drop_unscreenable`` they are given
-    up after ``max_rounds`` and flagged False in the returned ``"clean"`` mask [B] (their expected values
-    are not well posed and a caller leaves them out of its comparison); otherwise that raises."""
+    A uniform too close to the probability it is compared with, or to a CDF step, is always cured by
+    drawing again (``max_rounds`` is a safety net: exceeding it raises).  A small normaliser may not be:
+    some requests meet one on every path that is at all likely (both distributions peaked on the same
+    token).  Such a request is drawn again ``norm_rounds`` times; if a normaliser below ``min_norm`` is
+    still met, then with ``allow_small_norm`` the request is kept with uniforms whose margins are clean
+    and flagged False in the returned ``"clean"`` mask [B]: the oracle's diag then says where the first
+    small normaliser was met (``small_norm_plen``, ``small_norm_node``), and a caller compares what the
+    walk decided up to there, which does not depend on it.  Without ``allow_small_norm`` that raises."""
     th = np.asarray(w.theta, np.float32)[None] if thetas is None else np.asarray(thetas, np.float32)
     K = th.shape[0]
+    mars_ref.set_norm_floor(min_norm)
 
     def run(idx=None):
         pick = (lambda a: a) if idx is None else (lambda a: _sub(a, idx))
@@ -52,7 +60,9 @@ def screen_uniforms(w, guard: float = 1e-4, min_norm: float = 2e-2, max_rounds: 
                                 th[k] if idx is None else th[k][idx], w.temperature, pick(w.uniforms),
                                 pick(w.draft_probs), indicator) for k in range(K)]
 
-    clean = np.ones(w.logits.shape[0], bool)
+    B = w.logits.shape[0]
+    clean = np.ones(B, bool)
+    norm_tries = np.zeros(B, np.int64)
 
     def result(outs):
         r = outs[0] if thetas is None else {key: np.stack([o[key] for o in outs]) for key in outs[0]}
@@ -66,19 +76,26 @@ def screen_uniforms(w, guard: float = 1e-4, min_norm: float = 2e-2, max_rounds: 
         cdf_guard = guard
     rounds = 0
     while True:
-        dirty = np.zeros(w.uniforms.shape[0], bool)
+        margin_dirty = np.zeros(B, bool)
+        norm_dirty = np.zeros(B, bool)
         for o in outs:
             d = o["diag"]
-            dirty |= (d["min_accept_margin"] < guard) | (d["min_cdf_margin"] < cdf_guard) | (d["min_norm"] < min_norm)
-        bad = np.nonzero(dirty & clean)[0]
+            margin_dirty |= (d["min_accept_margin"] < guard) | (d["min_cdf_margin"] < cdf_guard)
+            norm_dirty |= d["min_norm"] < min_norm
+        gave_up = norm_dirty & ~margin_dirty & (norm_tries >= norm_rounds)
+        if gave_up.any():
+            if not allow_small_norm:
+                raise RuntimeError(f"residual normaliser below {min_norm} on every draw for requests "
+                                   f"{np.nonzero(gave_up)[0].tolist()}")
+            clean[gave_up] = False
+        clean[~norm_dirty] = True          # (a later draw may have found a path without a small normaliser)
+        bad = np.nonzero(margin_dirty | (norm_dirty & clean))[0]
         if bad.size == 0:
             return result(outs)
         rounds += 1
-        if rounds > max_rounds:
-            if not drop_unscreenable:
-                raise RuntimeError(f"uniform guard band not reached for requests {bad.tolist()}")
-            clean[bad] = False
-            return result(outs)
+        if rounds > max_rounds + norm_rounds:
+            raise RuntimeError(f"uniform guard band not reached for requests {bad.tolist()}")
+        norm_tries[bad] += norm_dirty[bad]
         for b in bad:
             rng = np.random.default_rng(np.random.SeedSequence([seed, rounds, int(b)]))
             w.uniforms[b] = rng.random(w.uniforms.shape[1], dtype=np.float32)

@@ -71,21 +71,79 @@ def bonus_prob_floor(ref_diag):
     return np.where(ref_diag["residual_passes"] > 0, RESIDUAL_ABS_TOL / z, 0.0)
 
 
-def compare(w, label=None, screened=True, cdf_guard=None, drop_unscreenable=False):
+MAX_SMALL_NORM_SHARE = 0.25   # at most this share of a workload's requests (one, in a tiny batch) may meet a
+                              # small normaliser whatever is drawn and be compared only up to it
+
+
+def assert_decisions_agree_in_both_precisions(w, ref, label):
+    """The low-margin test is decided in fp32 on both sides (what the library computes in); the plain
+    definition is the fp64 one.  A generated workload keeps its rows a guard band away from the threshold,
+    so the two must agree on every row -- the mirrored decision can then hide no disagreement.  (Hand-made
+    inputs that sit on a threshold on purpose carry no guard band and are exempt.)"""
+    if "guard" in getattr(w, "meta", {}):
+        assert np.array_equal(ref["stats"]["relax_ok"], ref["stats"]["relax_ok64"]), (
+            f"{label}: the fp32 and the fp64 low-margin decisions differ on guarded data")
+
+
+def assert_few_small_norm(clean, label):
+    n = int((~clean).sum())
+    allowed = max(1, int(np.ceil(MAX_SMALL_NORM_SHARE * clean.size)))
+    say(f"[info] {label}: {n} of {clean.size} requests meet a small normaliser on every draw: compared up to it")
+    assert n <= allowed, f"{label}: {n} of {clean.size} requests cannot be compared in full (at most {allowed})"
+
+
+def assert_prefix_parity(w, ref, outs, b, label, k=None):
+    """A request whose walk meets a residual normaliser below the floor on every likely path.  Up to that
+    point -- ``small_norm_plen`` accepted drafts, the rejections at ``small_norm_node`` before it -- nothing the
+    walk decided depends on the small normaliser, and the GPU must agree with the oracle on all of it; what
+    comes after need only be a valid outcome (a root-to-node chain, mask and codes consistent with it, a
+    token inside the vocabulary).  ``outs``: numpy outputs of the GPU for the whole batch (axis k first if given)."""
+    sel = (lambda a: a[b]) if k is None else (lambda a: a[k][b])
+    dg = sel(ref["diag"])
+    L = int(dg["small_norm_plen"])
+    assert L >= 0, f"{label}: request {b} is flagged but met no small normaliser"
+    rpath, gpath = sel(ref["path_idx"]), sel(outs["path_idx"])
+    glen = int(sel(outs["accept_len"]))
+    gmask, gdec = sel(outs["accept_mask"]), sel(outs["decision"])
+    assert glen >= L and np.array_equal(gpath[:L], rpath[:L]), f"{label}: request {b}: path prefix {gpath[:L]} vs {rpath[:L]}"
+    for node in rpath[:L]:
+        assert gdec[node] == sel(ref["decision"])[node], f"{label}: request {b}: code of node {node}"
+    par = w.tree_parent[b]
+    assert (gpath[:glen] > 0).all() and (gpath[glen:] == -1).all(), f"{label}: request {b}: path padding"
+    prev = 0
+    for node in gpath[:glen]:
+        assert par[node] == prev, f"{label}: request {b}: node {node} does not hang under {prev}"
+        prev = int(node)
+    if L == glen:
+        assert prev == int(dg["small_norm_node"]), f"{label}: request {b}: stopped at {prev}"
+    want_mask = np.zeros(w.N, np.uint8)
+    want_mask[0] = 1
+    want_mask[gpath[:glen]] = 1
+    assert np.array_equal(gmask, want_mask), f"{label}: request {b}: mask"
+    assert ((gdec != 0) == (want_mask != 0))[1:].all() and gdec[0] == 0, f"{label}: request {b}: codes off the path"
+    assert 0 <= int(sel(outs["bonus_token"])) < w.V and int(sel(outs["request_status"])) == 0
+
+
+def compare(w, label=None, screened=True, cdf_guard=None, allow_small_norm=False):
     """Run both sides on workload ``w`` (uniforms are screened in place first) and assert parity.
-    Returns a small summary dict.  With ``drop_unscreenable`` the requests whose uniforms cannot be kept
-    clear of the decision thresholds are left out of the per-request comparison (the row statistics,
-    which do not depend on uniforms, are still compared for every row)."""
+    Returns a small summary dict.  With ``allow_small_norm`` a request that meets a residual normaliser
+    below the screening floor whatever uniforms are drawn is compared up to that point
+    (``assert_prefix_parity``) instead of in full; their share is bounded.  The row statistics, which do
+    not depend on uniforms, are compared for every row."""
     label = label or w.name
     say(f"[case] {label}: B={w.B} N={w.N} V={w.V} dtype={w.dtype} T={w.temperature} "
         f"dense_q={w.draft_probs is not None}")
-    ref = screen.screen_uniforms(w, cdf_guard=cdf_guard, max_rounds=60 if drop_unscreenable else 200,
-                                 drop_unscreenable=drop_unscreenable) if screened else mars_ref.verify(
+    ref = screen.screen_uniforms(w, cdf_guard=cdf_guard, allow_small_norm=allow_small_norm) if screened else mars_ref.verify(
         w.logits, w.draft_tokens, w.tree_parent, w.theta, w.temperature, w.uniforms, w.draft_probs)
+    assert_decisions_agree_in_both_precisions(w, ref, label)
     clean = ref.get("clean", np.ones(w.B, bool))
-    if not clean.all():
-        say(f"[info] {label}: {int((~clean).sum())} of {w.B} requests cannot be screened and are left out")
     out = run_gpu(w)
+    if not clean.all():
+        assert_few_small_norm(clean, label)
+        outs_np = {key: getattr(out, key).cpu().numpy() for key in
+                   ("accept_len", "bonus_token", "request_status", "accept_mask", "path_idx", "decision")}
+        for b in np.nonzero(~clean)[0]:
+            assert_prefix_parity(w, ref, outs_np, int(b), label)
     sampling = w.temperature > 0
     for key in ("accept_len", "bonus_token", "request_status", "accept_mask", "path_idx", "decision"):
         g = getattr(out, key).cpu().numpy()
@@ -117,7 +175,7 @@ INDICATOR_CODE = {"logit_ratio": M.MARS_IND_LOGIT_RATIO, "prob_ratio": M.MARS_IN
 
 
 def compare_ex(w, label=None, indicator="logit_ratio", thetas=None, cdf_guard=None, commit=True,
-               drop_unscreenable=False):
+               allow_small_norm=False):
     """mars_verify_ex against the oracle: chosen indicator, optional sweep thetas[K,B] (every output
     with a leading K axis), committed sequence and kept cache rows.  Same bar as ``compare``."""
     label = label or w.name
@@ -126,16 +184,23 @@ def compare_ex(w, label=None, indicator="logit_ratio", thetas=None, cdf_guard=No
     say(f"[case] {label}: B={w.B} N={w.N} V={w.V} dtype={w.dtype} T={w.temperature} "
         f"dense_q={w.draft_probs is not None} indicator={indicator} K={K} commit={commit}")
     ref = screen.screen_uniforms(w, cdf_guard=cdf_guard, indicator=code, thetas=thetas,
-                                 max_rounds=60 if drop_unscreenable else 200, drop_unscreenable=drop_unscreenable)
-    clean = ref["clean"]                       # [B]: requests whose expected values are well posed
-    if not clean.all():
-        say(f"[info] {label}: {int((~clean).sum())} of {w.B} requests cannot be screened and are left out")
+                                 allow_small_norm=allow_small_norm)
+    assert_decisions_agree_in_both_precisions(w, ref, label)
+    clean = ref["clean"]                       # [B]: requests compared in full
     d = to_device(w)
     th = d["theta"] if thetas is None else torch.from_numpy(np.ascontiguousarray(thetas, dtype=np.float32)).to(
         d["logits"].device)
     out = M.mars_verify_ex(d["logits"], d["draft_tokens"], d["tree_parent"], th, w.temperature, d["uniforms"],
                            d["draft_probs"], indicator=code, n_theta=K, want_commit=commit)
     torch.cuda.synchronize()
+    if not clean.all():
+        assert_few_small_norm(clean, label)
+        outs_np = {key: getattr(out, key).cpu().numpy() for key in
+                   ("accept_len", "bonus_token", "request_status", "accept_mask", "path_idx", "decision")}
+        for b in np.nonzero(~clean)[0]:
+            for k in (range(K) if thetas is not None else [None]):
+                if (ref["diag"][b] if k is None else ref["diag"][k][b])["small_norm_plen"] >= 0:
+                    assert_prefix_parity(w, ref, outs_np, int(b), label, k)
     sampling = w.temperature > 0
     for key in ("accept_len", "bonus_token", "request_status", "accept_mask", "path_idx", "decision"):
         g = getattr(out, key).cpu().numpy()

@@ -260,4 +260,62 @@ def test_draft_distribution_stored_as_bf16(dtype, B):
     # sampling kernel (few requests, many work-groups each) and in the streaming form (many requests)
     w = make_config(2, B=B, N=20, V=40008, dtype=dtype, tree={"kind": "tree", "depth": 4, "max_children": 3})
     w.draft_probs = f32_to_bf16_bits(w.draft_probs)
-    compare(w, label=f"bf16_q_{dtype}_B{B}", cdf_guard=5e-6, drop_unscreenable=True)
+    compare(w, label=f"bf16_q_{dtype}_B{B}", cdf_guard=5e-6, allow_small_norm=True)
+
+
+# ----------------------------------------------------------------------------- wide trees: long residual chains
+def wide_tree_workload(B, V, dtype, dense, seed):
+    """Trees of the paper's width (top-k = 10 children per expanded node, Sec. 4.1 implementation details) built
+    so that long runs of siblings are rejected at one node: the root has ten children of which the first five
+    are rejected and the sixth accepted; that node has ten children, nine rejected, the tenth accepted; its ten
+    children are all rejected, so the final token is drawn from a ten-fold residual.  A rejected child carries
+    a token the target gives far less mass than the draft distribution does (dense q: q > 50 p; one-hot: p below
+    1e-4) and a high uniform, an accepted one the token where the target exceeds the draft most, and a low one.
+    Inputs only: the expected outputs are the oracle's, whatever path the uniforms (re-drawn by the screening
+    where they come too close to a threshold) finally produce."""
+    from mars_inputs import bf16_bits_to_f32
+    fan, N, T = 10, 31, 0.8
+    w = make_workload(f"wide_B{B}_V{V}_{dtype}_{'dense' if dense else 'onehot'}", B=B, N=N, V=V, dtype=dtype,
+                      temperature=T, tree={"kind": "chain"}, plant_frac=0.5, dense_q=dense, seed=seed)
+    par = np.array([-1] + [0] * fan + [6] * fan + [20] * fan, np.int32)
+    accepted = {6, 20}
+    rng = np.random.default_rng(seed)
+    for b in range(B):
+        w.tree_parent[b] = par
+        for c in (0, 6, 20):
+            row = bf16_bits_to_f32(w.logits[b, c]) if dtype == "bf16" else w.logits[b, c]
+            x = row.astype(np.float64) / np.float64(np.float32(T))
+            p = np.exp(x - x.max())
+            p /= p.sum()
+            top2 = set(np.argsort(-row, kind="stable")[:2].tolist())
+            if dense:
+                q = w.draft_probs[b, c].astype(np.float64)
+                cand = np.nonzero(q > 50 * p)[0]
+                best = int(np.argmax(p - q))
+            else:
+                cand = np.nonzero(p < 1e-4)[0]
+                best = int(np.argmax(p))
+            cand = [int(t) for t in rng.permutation(cand) if int(t) not in top2 and int(t) != best][:fan]
+            assert len(cand) == fan, "not enough unlikely tokens in this row"
+            for j, k in enumerate(np.nonzero(par == c)[0]):
+                if int(k) in accepted:
+                    w.draft_tokens[b, k], w.uniforms[b, k] = best, 0.003
+                else:
+                    w.draft_tokens[b, k], w.uniforms[b, k] = cand[j], 0.9
+    return w
+
+
+@pytest.mark.parametrize("dtype,dense,B,V", [("bf16", True, 2, 40008), ("f32", True, 3, 24000),
+                                             ("bf16", False, 2, 40008), ("f32", False, 3, 24000),
+                                             ("bf16", True, 128, 40008), ("f32", False, 128, 32768)])
+def test_ten_children_per_node_with_five_nine_and_ten_rejections(dtype, dense, B, V):
+    # Residual chains longer than the four entries the walk keeps in registers: entries five to ten live in
+    # LDS, both where a single probability is evaluated against the chain and where a slice is brought up
+    # to date with it.  Few requests: slices resident in registers; 128 requests: slices streamed.
+    from oracle import screen
+    w = wide_tree_workload(B, V, dtype, dense, seed=700 + B)
+    ref = screen.screen_uniforms(w, cdf_guard=5e-6, allow_small_norm=True)
+    rej = ref["diag"]["residual_passes"]
+    say(f"[info] wide trees: rejections per request {rej[:8].tolist()} accept_len {ref['accept_len'][:8].tolist()}")
+    assert (rej >= 20).mean() >= 0.5, "the workload no longer produces long runs of rejected siblings"
+    compare(w, cdf_guard=5e-6, allow_small_norm=True)
