@@ -10,28 +10,31 @@ input sets are rotated so that a step never finds its logits in the 256 MB memor
 
 ``--workload`` selects what a step is:
   headline  mars_verify on the headline configuration (the default; the line the metric is quoted on)
+  cfg0 / cfg1_greedy / cfg1_sampling / cfg3 / cfg4
+            mars_verify on the other stated configurations: a greedy chain of 8 drafts over 32 000 entries
+            (fp32); one 60-node tree over 151 936 entries at T = 0 and at T = 1 (one-hot draft); 64 greedy
+            chains over 128 256 entries with a threshold per request; 256 trees of 26 nodes over 151 936
+            fp32 entries at T = 1 (4 GB of logits, one input set: it exceeds every cache by itself)
   commit    the same through mars_verify_ex with the committed sequence and the kept cache rows
   sweep7    the same with seven thresholds per request (0.84 .. 0.96) from one read of the logits
   margin    mars_margin_stats on the same logits (top-2 statistics per row and their histograms)
   spd       mars_verify on chains of 6 drafts with a dense draft distribution, B = 128, T = 1
-  single_greedy / single_sampling
-            mars_verify on one request (a 60-node tree, V = 151 936, bf16) at T = 0 / at T = 1 with a
-            one-hot draft distribution: the latency of a single pass, issued on one stream
   lmhead    mars_lmhead_verify: greedy verification from the last hidden states (H = 4096) and the
             LM-head weight [151 936, 4096], the logits never written to memory; its roofline object
             is the matrix-core one (bf16 MFMA peak) of the fused kernel
 
-The timed steps are issued round-robin on ``--streams`` HIP streams (default 2; 1 for the
-single-request workloads), each with its own
-workspace and outputs: the library keeps no state and calls with different workspaces may overlap,
-so the latency-bound per-request kernel of one step runs beside the bandwidth-bound row reduction
-of the next, as a server verifying two micro-batches would have it.  ``value`` is the throughput of
-that; the line also carries the one-stream throughput and the latency of single calls
-(``config.single_stream_*``, ``config.call_us_*``).
+``value`` is the throughput of the passes issued one after the other on ONE stream: what one caller of
+the library sees.  Beside it the line carries the throughput with the steps issued round-robin on
+``--streams`` HIP streams (default 2; 1 = not measured), each with its own workspace and outputs
+(``config.overlapped_*``): the library keeps no state and calls with different workspaces may
+overlap, so the latency-bound per-request kernel of one step runs beside the bandwidth-bound row
+reduction of the next, as a server verifying two micro-batches would have it; and the latency of
+single calls (``config.call_us_*``).
 
-Prints ONE JSON line with the whole-job rows/s, the HBM roofline of the dominant kernel (the row
-reduction, timed by itself with HIP events on the stream it runs on) and the CPU oracle timed on
-the host cores of the same box.
+Prints ONE JSON line with the whole-job rows/s, two HBM roofline objects -- ``roofline``: the
+dominant kernel (the row reduction, timed by itself with HIP events on the stream it runs on);
+``roofline_pass``: the whole call, the bytes of the logits over the time of one call -- and the CPU
+oracle timed on the host cores of the same box.
 """
 import argparse
 import hashlib
@@ -63,12 +66,18 @@ WORKLOADS = {
                                "of z1, z2/z1, p2/p1 (40/50/50 cells)"),
     "spd": dict(cfg=5, what="chains of 6 drafts (N=7), B=128, V=151936, bf16 logits, dense fp32 draft distribution, "
                             "T=1, theta=0.9"),
-    "single_greedy": dict(cfg=1, temperature=0.0, streams=1,
-                          what="configs[1] with T=0: one request, a 60-node tree, V=151936, bf16 logits, theta=0.9 "
-                               "(the latency of a single greedy pass)"),
-    "single_sampling": dict(cfg=1, streams=1,
-                            what="configs[1] with T=1.0 and a one-hot draft distribution: one request, a 60-node "
-                                 "tree, V=151936, bf16 logits, theta=0.9 (the latency of a single sampling pass)"),
+    "cfg0": dict(cfg=0, streams=1, what="configs[0]: greedy, B=1, chain of 8 drafts (N=9), V=32000, fp32 logits, "
+                                         "theta=0.9 (1.15 MB of logits: a latency, the inputs stay in cache)"),
+    "cfg1_greedy": dict(cfg=1, temperature=0.0, streams=1,
+                        what="configs[1] at T=0: B=1, a 60-node tree, V=151936, bf16 logits, theta=0.9"),
+    "cfg1_sampling": dict(cfg=1, streams=1,
+                          what="configs[1] at T=1.0 with a one-hot draft distribution: B=1, a 60-node tree, V=151936, "
+                               "bf16 logits, theta=0.9"),
+    "cfg3": dict(cfg=3, what="configs[3]: greedy, B=64, chains of 8 drafts (N=9), V=128256, bf16 logits, Gumbel(0,2) "
+                             "background, a threshold per request from {0.85, 0.9, 0.95}"),
+    "cfg4": dict(cfg=4, buffers=1, steps=40, warmup=4,
+                 what="configs[4]: sampling T=1.0, B=256, a 26-node tree per request, V=151936, fp32 logits (4.05 GB, "
+                      "one input set), one-hot draft distribution, theta=0.9"),
     "lmhead": dict(cfg=None, what="greedy verification from hidden states: B=16, 60-node tree per request, H=4096, "
                                   "V=151936, bf16 hidden states and LM-head weight, theta=0.9; logits formed, reduced "
                                   "and dropped inside one kernel"),
@@ -199,6 +208,20 @@ def main_lmhead(args) -> int:
     k_ms = e0.elapsed_time(e1) / args.steps
     flops = 2.0 * rows * H * V
     achieved = flops / (k_ms * 1e-3) / 1e12
+    # For context: the same product by the library GEMM, which also has to write the logits (an unfused
+    # pipeline then still runs the row reduction and the per-request kernel over them).
+    h2 = d["h"].view(torch.bfloat16).reshape(rows, H)
+    w2 = d["w"].view(torch.bfloat16)
+    for _ in range(3):
+        torch.matmul(h2, w2.t())
+    torch.cuda.synchronize()
+    n_mm = max(4, min(args.steps, 30))
+    e0.record()
+    for _ in range(n_mm):
+        torch.matmul(h2, w2.t())
+    e1.record()
+    torch.cuda.synchronize()
+    gemm_us = e0.elapsed_time(e1) / n_mm * 1e3
     result = {
         "metric": "rows/s + achieved bf16 MFMA TFLOP/s vs peak, workload 'lmhead'",
         "value": rows * args.steps / elapsed, "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -207,6 +230,7 @@ def main_lmhead(args) -> int:
         "config": {"workload": WORKLOADS["lmhead"]["what"], "B": B, "N": N, "H": H, "V": V, "rows_per_step": rows,
                    "streams": 1, "mean_tau": tau, "requests_with_nonzero_status": statuses,
                    "weight_bytes": V * H * 2, "weight_stream_GBps": V * H * 2 / (k_ms * 1e-3) / 1e9,
+                   "library_gemm_us": gemm_us,
                    "input_generation_s": round(t_gen, 1)},
         "roofline": {"bound": "mfma", "kernel": "lmhead_reduce_kernel<192>", "achieved": achieved,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
@@ -237,12 +261,12 @@ def main_lmhead(args) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 400; 40 for cfg4)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default 40; 4 for cfg4)")
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="headline")
     ap.add_argument("--streams", type=int, default=None,
-                    help="HIP streams the timed steps alternate over (default: 2; 1 for the single-request workloads, "
-                         "whose figure is a latency)")
+                    help="HIP streams of the additional overlapped measurement (default: 2; 1 = none, also the default "
+                         "for the single-request workloads, whose figure is a latency)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for hardware-counter runs: a few launches of the row reduction on the headline "
@@ -253,6 +277,10 @@ def main() -> int:
               "exchange between GPUs; run it with --gpus 1", file=sys.stderr)
         return 2
 
+    if args.steps is None:
+        args.steps = WORKLOADS[args.workload].get("steps", 400)
+    if args.warmup is None:
+        args.warmup = WORKLOADS[args.workload].get("warmup", 40)
     if args.workload == "lmhead":
         return main_lmhead(args)
 
@@ -280,9 +308,10 @@ def main() -> int:
     if wl == "sweep7":
         spec["sweep_thetas"] = SWEEP
 
+    n_buffers = WORKLOADS[wl].get("buffers", N_BUFFERS)
     t_gen = time.perf_counter()
     sets, host0 = [], None
-    for k in range(N_BUFFERS):
+    for k in range(n_buffers):
         w = make_workload(f"{name}_set{k}", seed=2 + 100 * k, **spec)
         if k == 0:
             host0 = w
@@ -308,8 +337,8 @@ def main() -> int:
 
     def step(i, j=0):
         """One pass over input set i with the workspace and outputs of slot j, on the current stream."""
-        s = sets[i % N_BUFFERS]
-        if wl in ("headline", "spd", "single_greedy", "single_sampling"):
+        s = sets[i % n_buffers]
+        if wl in ("headline", "spd") or wl.startswith("cfg"):
             M.mars_verify(s["logits"], s["tok"], s["par"], s["theta"], T, s["u"], s["q"], outs[j], wss[j])
         elif wl == "margin":
             M.mars_margin_stats(s["logits"], s["theta"], T, MARGIN_RANGES, MARGIN_BINS, margin_rows[j],
@@ -322,8 +351,8 @@ def main() -> int:
         # logits tensor (read) and as many again (write): the known quantity the counters are scaled by.
         dst = torch.empty_like(sets[0]["logits"])
         for i in range(6):
-            dst.copy_(sets[i % N_BUFFERS]["logits"])
-            M.mars_row_reduce(sets[i % N_BUFFERS]["logits"], k1_temperature, ws)
+            dst.copy_(sets[i % n_buffers]["logits"])
+            M.mars_row_reduce(sets[i % n_buffers]["logits"], k1_temperature, ws)
         for i in range(6):  # and the whole pass, so that the per-request kernel is counted too
             step(i)
         torch.cuda.synchronize()
@@ -348,15 +377,18 @@ def main() -> int:
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
-    timed(args.warmup, n_streams)
-    elapsed = timed(args.steps, n_streams)
+    # The figure of the line: the passes one after the other on one stream.
+    timed(args.warmup, 1)
+    elapsed = timed(args.steps, 1)
     ms_per_step = elapsed / args.steps * 1e3
     value = rows * args.steps / elapsed
     tau = None if wl == "margin" else (out.accept_len.float().reshape(K, B).mean(dim=1) + 1.0).tolist()
+    # Beside it: the same passes round-robin over several streams (calls overlap).
+    overlapped = None
+    if n_streams > 1:
+        timed(min(args.warmup, 10), n_streams)
+        overlapped = timed(args.steps, n_streams)
     statuses = 0 if wl == "margin" else int(sum((o.request_status != 0).sum().item() for o in outs))
-    # the same passes one after the other on one stream
-    timed(min(args.warmup, 10), 0)
-    single_elapsed = timed(args.steps, 0)
 
     # Spread of one call: HIP events around each of up to 200 further calls (no host sync between them).
     n_ev = min(args.steps, 200)
@@ -371,12 +403,12 @@ def main() -> int:
 
     # The dominant kernel by itself: HIP events on the stream the kernel is launched on.
     for i in range(min(args.warmup, 10)):
-        M.mars_row_reduce(sets[i % N_BUFFERS]["logits"], k1_temperature, ws)
+        M.mars_row_reduce(sets[i % n_buffers]["logits"], k1_temperature, ws)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record()
     for i in range(args.steps):
-        M.mars_row_reduce(sets[i % N_BUFFERS]["logits"], k1_temperature, ws)
+        M.mars_row_reduce(sets[i % n_buffers]["logits"], k1_temperature, ws)
     e1.record()
     torch.cuda.synchronize()
     k1_ms = e0.elapsed_time(e1) / args.steps
@@ -384,11 +416,28 @@ def main() -> int:
     splits = max(1, min((target + rows - 1) // rows, V // 8192))  # 2 splits per row for 960 rows
     algo_bytes = rows * V * elt + rows * splits * WAVES_PER_GROUP * PARTIAL_BYTES
     achieved = algo_bytes / (k1_ms * 1e-3) / 1e9
+    # What the memory system gives a plain kernel on the same tensors: a device copy (as many bytes written as read).
+    dst = torch.empty_like(sets[0]["logits"])
+    for i in range(3):
+        dst.copy_(sets[i % n_buffers]["logits"])
+    torch.cuda.synchronize()
+    n_copy = max(4, min(args.steps, 50))
+    e0.record()
+    for i in range(n_copy):
+        dst.copy_(sets[i % n_buffers]["logits"])
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2.0 * rows * V * elt / (e0.elapsed_time(e1) / n_copy * 1e-3) / 1e9
+    del dst
+    traffic = measured_traffic() if wl in ("headline", "commit", "sweep7") else None
+    pass_bytes = rows * V * elt  # the logits, read once; everything else a pass touches is noise next to them
+    pass_gbps = pass_bytes / (ms_per_step * 1e-3) / 1e9
 
     metric = "verify rows/s + achieved HBM GB/s vs peak, B=16 tree-60 V=151936 bf16"
     if wl != "headline":
         metric = f"rows/s + achieved HBM GB/s vs peak, workload '{wl}'"
-    k1_name = "row_reduce_kernel<bf16, 8 per load, %s>" % ("top-2 only" if k1_temperature == 0.0 else "sampling")
+    k1_name = "row_reduce_kernel<%s, %d per load, %s>" % (spec["dtype"], 16 // elt,
+                                                          "top-2 only" if k1_temperature == 0.0 else "sampling")
     result = {
         "metric": metric,
         "value": value,
@@ -400,30 +449,36 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f32",   # the arithmetic of the path (statistics and probabilities in fp32); storage: logits_dtype
         "data": "synthetic",
         "config": {"workload": WORKLOADS[wl]["what"],
                    "B": B, "N": N, "V": V, "rows_per_step": rows, "logits_dtype": spec["dtype"],
-                   "temperature": T, "thresholds_per_request": K, "input_sets_rotated": N_BUFFERS, "mean_tau": tau,
-                   "streams": n_streams, "requests_with_nonzero_status": statuses,
-                   "single_stream_ms_per_step": single_elapsed / args.steps * 1e3,
-                   "single_stream_rows_per_s": rows * args.steps / single_elapsed,
-                   "whole_pass_logits_GBps": rows * V * elt / (ms_per_step * 1e-3) / 1e9,
-                   "single_stream_pass_hbm_GBps": (measured_pass_traffic() / (single_elapsed / args.steps) / 1e9
-                                                   if wl == "headline" and measured_pass_traffic() else None),
+                   "temperature": T, "thresholds_per_request": K, "input_sets_rotated": n_buffers, "mean_tau": tau,
+                   "streams": 1, "requests_with_nonzero_status": statuses,
+                   "overlapped_streams": n_streams if overlapped else None,
+                   "overlapped_ms_per_step": overlapped / args.steps * 1e3 if overlapped else None,
+                   "overlapped_rows_per_s": rows * args.steps / overlapped if overlapped else None,
+                   "pass_hbm_traffic_GBps": (measured_pass_traffic() / (ms_per_step * 1e-3) / 1e9
+                                             if wl == "headline" and measured_pass_traffic() else None),
                    "call_us_p10": pct[10], "call_us_median": pct[50], "call_us_p90": pct[90],
+                   "device_copy_GBps": copy_gbps,
                    "input_generation_s": round(t_gen, 1)},
         "roofline": {"bound": "hbm", "kernel": k1_name,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic() if wl in ("headline", "commit", "sweep7") else None,
+                     "traffic": traffic,
+                     "traffic_stale": bool(traffic is None and wl in ("headline", "commit", "sweep7")),
                      "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_us": k1_ms * 1e3},
+        # the whole call against the same roofline: the logits are read once per pass, whatever else it does
+        "roofline_pass": {"bound": "hbm", "what": "one call on one stream, all kernels", "achieved": pass_gbps,
+                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pass_gbps / HBM_PEAK_GBS,
+                          "algorithmic_bytes_per_call": pass_bytes, "ms_per_call": ms_per_step},
     }
 
     if not args.no_cpu_baseline:
         from oracle import mars_ref
-        cores = os.cpu_count() or 1
-        cores = min(cores, 16) if "OMP_NUM_THREADS" not in os.environ else int(os.environ["OMP_NUM_THREADS"])
+        found = os.cpu_count() or 1
+        cores = min(found, 16) if "OMP_NUM_THREADS" not in os.environ else int(os.environ["OMP_NUM_THREADS"])
 
         def oracle_pass():
             h = host0
@@ -449,7 +504,8 @@ def main() -> int:
         t = time.perf_counter()
         oracle_pass()
         one_s = time.perf_counter() - t
-        result["cpu_baseline"] = {"value": rows * reps / cpu_s, "unit": "rows/s", "cores": cores, "kind": "oracle",
+        result["cpu_baseline"] = {"value": rows * reps / cpu_s, "unit": "rows/s", "cores": cores,
+                                  "host_cores_found": found, "kind": "oracle",
                                   "sample": f"the whole workload ({rows} rows, input set 0), {reps} passes, "
                                             f"{cpu_s:.1f} s wall",
                                   "single_thread_value": rows / one_s}

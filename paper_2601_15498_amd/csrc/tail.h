@@ -519,7 +519,6 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   constexpr int NW = NT / kWave;
   __shared__ int16_t sh_par[MARS_MAX_NODES];     // parent of every node
   __shared__ int32_t sh_tok[MARS_MAX_NODES];     // draft token of every node
-  __shared__ unsigned long long sh_kids[MARS_MAX_NODES / kWave];  // bit i of word w: node 64w+i is a child of the current node
   __shared__ float sh_zx[MARS_MAX_NODES];        // logit of the node's token in its parent's row
   __shared__ float sh_qx[MARS_MAX_NODES];        // draft probability of the node's token (1 if one-hot)
   __shared__ int32_t sh_ctok[MARS_MAX_NODES];    // residual chain: rejected tokens
@@ -630,31 +629,41 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   rv.V = V; rv.vec_ok = vec_ok; rv.c = c;
   rv.ch.tok = sh_ctok; rv.ch.inv_norm = sh_cinv; rv.ch.n = 0;
   float fc[kResident][8], qv[kResident][8];  // resident slice: current f and the draft probabilities
-  bool have = false;                          // fc / qv hold this node's slice
+  bool have = false;                          // fc holds the current f of this node's slice
+  bool raw = false;                           // fc / qv hold the node's raw slice (logits, draft probabilities)
   int applied = 0;                            // chain entries already worked into fc
 
-  // Bring the resident slice up to date with the chain (loading it on first use).
+  // The loads of the resident slice, issued when a pass first needs it.  (Issuing them on arrival at every
+  // node, in case a rejection follows, was tried: the next node's loads then have to wait for the registers
+  // of the previous node's, and every accepted draft costs a trip to memory -- 86 instead of 80 us per pass.)
+  auto load_resident = [&]() {
+#pragma unroll
+    for (int i = 0; i < kResident; ++i) {
+      const int gi = g_begin + i * NT + tid;
+      if (gi < g_end) {
+        rv.load(gi, fc[i], qv[i]);
+      } else {  // nothing there: f = 0 and q = 0 contribute nothing
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { fc[i][e] = neg_inf(); qv[i][e] = 0.0f; }
+      }
+      if (!dense) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qv[i][e] = 0.0f;
+      }
+    }
+    raw = true;
+    have = false;
+  };
+  // Bring the resident slice up to date with the chain (turning the raw slice into f on first use).
   auto refresh_resident = [&]() {
     if (!have) {
-#pragma unroll
-      for (int i = 0; i < kResident; ++i) {
-        const int gi = g_begin + i * NT + tid;
-        if (gi < g_end) {
-          rv.load(gi, fc[i], qv[i]);
-        } else {  // nothing there: f = 0 and q = 0 contribute nothing
-#pragma unroll
-          for (int e = 0; e < 8; ++e) { fc[i][e] = neg_inf(); qv[i][e] = 0.0f; }
-        }
-        if (!dense) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) qv[i][e] = 0.0f;
-        }
-      }
+      if (!raw) load_resident();
 #pragma unroll
       for (int i = 0; i < kResident; ++i)
 #pragma unroll
         for (int e = 0; e < 8; ++e)
           fc[i][e] = __builtin_amdgcn_exp2f((fc[i][e] - rv.z1) * c) * rv.inv_S;  // softmax term (Eq. 3)
+      raw = false;
       have = true;
       applied = 0;
     }
@@ -688,27 +697,25 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
     rv.ch.n = 0;
     pending_norm = false;
     have = false;
+    raw = false;
     applied = 0;
-    // children of cnode, as bit masks over the nodes (increasing node index = increasing bit).
-    // The barrier keeps a wave that has just accepted a child from overwriting the masks of the
-    // previous node while another wave is still reading them.
-    __syncthreads();
-    for (int wd = wave; wd < nwords; wd += NW) {
+    // The children of cnode as bit masks over the nodes (increasing node index = increasing bit), 64
+    // nodes to a word.  Every wave forms the words for itself from the parents in LDS: no wave waits for
+    // another one on the way down the tree.
+    auto kids_word = [&](int wd) {
       const int i = wd * kWave + lane;
-      const unsigned long long m = __ballot(i < N && i > cnode && sh_par[i] == cnode);
-      if (lane == 0) sh_kids[wd] = m;
-    }
-    __syncthreads();
+      return __ballot(i < N && i > cnode && sh_par[i] == cnode);
+    };
     int accepted = -1;
     int wd = cnode / kWave;              // children have larger indices than their parent
-    unsigned long long bits = sh_kids[wd];
+    unsigned long long bits = kids_word(wd);
     for (;;) {
-      while (bits == 0ull && wd + 1 < nwords) bits = sh_kids[++wd];
+      while (bits == 0ull && wd + 1 < nwords) bits = kids_word(++wd);
       if (bits == 0ull) break;
       const int k = wd * kWave + __ffsll(static_cast<long long>(bits)) - 1;
       bits &= bits - 1;
       bool more = bits != 0ull;          // does cnode have further children after k?
-      for (int w2 = wd + 1; w2 < nwords && !more; ++w2) more = sh_kids[w2] != 0ull;
+      for (int w2 = wd + 1; w2 < nwords && !more; ++w2) more = kids_word(w2) != 0ull;
       const int x = sh_tok[k];
       // Every thread takes the decision for itself from the same LDS-resident inputs (same
       // instructions, same bits): no broadcast and no barrier per tested child.
@@ -940,6 +947,7 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
     pending_norm = false;
     last_norm = 0.0f;
     have = false;
+    raw = false;
     applied = 0;
     __syncthreads();
   }
