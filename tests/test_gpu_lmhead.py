@@ -15,7 +15,7 @@ from mars_inputs.lmhead import LMHEAD_CONFIGS, make_lmhead_workload
 from oracle import lmhead_ref, mars_ref
 from paper_2601_15498_amd import binding as M
 
-from gpu_util import say
+from tests.gpu_util import say
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -172,6 +172,28 @@ def test_malformed_requests_are_flagged():
     torch.cuda.synchronize()
     assert_requests_match(out, ref, "bad")
     assert np.array_equal(ref["accept_len"][[0, 3]], ref0["accept_len"][[0, 3]])
+
+
+def test_batch_shape_does_not_change_the_result_on_screened_inputs():
+    # The order in which a row's products are added depends on the launch plan (slab height, runs of tiles), so
+    # on the batch shape; on inputs whose deciding logits keep clear of the bf16 rounding boundaries that must not
+    # show.  The same requests verified in one batch (a tall slab, many rows) and one by one (a slab of 64 rows,
+    # a different split of the vocabulary over the work-groups) give identical rows and identical outcomes.
+    w = make_lmhead_workload("plan", B=7, N=30, H=512, V=20000, tree={"kind": "tree", "depth": 4, "max_children": 4},
+                             seed=17)
+    ref = lmhead_ref.screen_lmhead(w)
+    d = to_device(w)
+    whole = M.mars_lmhead_verify(d["h"], d["w"], d["tok"], d["par"], d["th"])
+    torch.cuda.synchronize()
+    assert_rows_match(whole.stats, ref["stats"], "plan: one batch")
+    assert_requests_match(whole, ref, "plan: one batch")
+    for b in range(w.B):
+        one = M.mars_lmhead_verify(d["h"][b:b + 1].contiguous(), d["w"], d["tok"][b:b + 1].contiguous(),
+                                   d["par"][b:b + 1].contiguous(), d["th"][b:b + 1].contiguous())
+        torch.cuda.synchronize()
+        for key in ("accept_len", "bonus_token", "path_idx", "accept_mask", "decision"):
+            assert torch.equal(getattr(one, key)[0], getattr(whole, key)[b]), (b, key)
+        assert torch.equal(one.stats.view(-1, M.ROW_STAT_WORDS), whole.stats.view(w.B, w.N, M.ROW_STAT_WORDS)[b]), b
 
 
 def test_calls_on_two_streams_and_repeated_calls_agree():
