@@ -1,4 +1,4 @@
-// Row reduction: per (row, split, wave) the two largest logits with their indices under
+// Row reduction: per (row, split) the two largest logits with their indices under
 // (value desc, index asc) and, in sampling mode, the sum of exp2(z*c - ref).
 // One streaming read of the logits; this is the HBM-bound kernel of the pass
 // (paper Sec. 3.3 top-2 identification, Eq. 3 softmax normaliser).
@@ -11,9 +11,10 @@
 // stream the few lanes that can hold a candidate look through their LDS copy (and, rarely,
 // reload the second batch) and produce exact (value, index) pairs.
 //
-// Every wave works for itself from the first load to its own partial result: there is no
-// barrier and no cross-wave traffic in the kernel, so a wave that has finished leaves the
-// memory pipeline to the others instead of holding them at a rendezvous.
+// Every wave works for itself from the first load to its own result: there is no barrier and
+// no cross-wave traffic while the stream runs, so a wave that has finished leaves the memory
+// pipeline to the others instead of holding them at a rendezvous.  The waves meet once, at the
+// very end, to fold their eight results into the work-group's one.
 #pragma once
 
 #include "common.h"
@@ -130,6 +131,12 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
 
   // Raw copy of every lane's best batch (vector j of lane t at [j][t]: conflict-free 16-byte rows).
   __shared__ Vec<T, EPV> sh_best[U][kRowThreads];
+  // Results of the eight waves and the number of waves that have theirs (cleared here; the only barrier
+  // of the kernel stands behind every wave's first loads, where nobody has anything to wait for yet).
+  __shared__ unsigned long long sh_k[NW][2];
+  __shared__ float sh_s[NW], sh_ref[NW];
+  __shared__ int sh_done;
+  if (tid == 0) sh_done = 0;
 
   Vec<T, EPV> bufA[U], bufB[U];
 
@@ -219,6 +226,7 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   int k = 0;
   if (nfull > 2) {
     load_full(bufA, 0);
+    __syncthreads();
     for (; k + 2 < nfull; k += 2) {
       load_full(bufB, k + 1);
       process(bufA, k);
@@ -227,6 +235,8 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
     }
     process(bufA, k);
     ++k;
+  } else {
+    __syncthreads();
   }
 #pragma unroll 1
   for (; k < nb; ++k) {
@@ -280,18 +290,40 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   }
   float ws = 0.0f;
   if (SAMPLING) ws = wave_sum(s);
+  // The wave that is last to have its result folds the eight into the work-group's partial result; the
+  // others leave at once.  (LDS operations of one wave are performed in order, so a wave that sees the
+  // count complete sees every result behind it.)  The kernel behind this one then reads one partial
+  // result per (row, split) instead of eight -- on its critical path, where this merge is not.
+  int last = 0;
+  if (lane == 0) {
+    sh_k[wave][0] = K1; sh_k[wave][1] = K2;
+    sh_s[wave] = ws; sh_ref[wave] = ref_c;
+    last = __hip_atomic_fetch_add(&sh_done, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP) == NW - 1;
+  }
+  if (!__builtin_amdgcn_readfirstlane(last)) return;
+  static_assert(NW == 8, "three butterfly steps merge eight waves");
+  unsigned long long B1 = 0, B2 = 0;
+  float R = -3.0e38f;
+  double S = 0.0;
+  if (lane < NW) {
+    B1 = sh_k[lane][0]; B2 = sh_k[lane][1];
+    if (SAMPLING && sh_s[lane] > 0.0f) { R = sh_ref[lane]; S = static_cast<double>(sh_s[lane]); }
+  }
+  merge_step<kDppXor1>(B1, B2, R, S);
+  merge_step<kDppXor2>(B1, B2, R, S);
+  merge_step<kDppHalfMirror>(B1, B2, R, S);
   if (lane == 0) {
     Partial out;
     out.z1 = neg_inf(); out.id1 = -1; out.z2 = neg_inf(); out.id2 = -1; out.s = 0.0f; out.ref = 0.0f;
-    if (K1 != 0ull) { out.z1 = key_value(K1); out.id1 = key_index(K1); }
-    if (K2 != 0ull) { out.z2 = key_value(K2); out.id2 = key_index(K2); }
-    if (SAMPLING && ws > 0.0f) { out.s = ws; out.ref = ref_c; }
-    partials[static_cast<size_t>(item) * NW + wave] = out;
+    if (B1 != 0ull) { out.z1 = key_value(B1); out.id1 = key_index(B1); }
+    if (B2 != 0ull) { out.z2 = key_value(B2); out.id2 = key_index(B2); }
+    if (SAMPLING && S > 0.0) { out.s = static_cast<float>(S); out.ref = R; }
+    partials[item] = out;
   }
 }
 
-// Partial results per (row, split): one per wave of the work-group.
-constexpr int kPartsPerItem = kRowThreads / kWave;
+// Partial results per (row, split).
+constexpr int kPartsPerItem = 1;
 
 // Merge the partial results of every row into the statistics table (16 rows per work-group).
 __global__ __launch_bounds__(256) void merge_stats_kernel(const Partial* __restrict__ partials, int rows, int N,

@@ -248,6 +248,21 @@ __device__ __forceinline__ float eval_f(float z, float q, int v, float z1, float
   return f;
 }
 
+// A child tested against the plain softmax of its parent's row (no rejection at that node yet): the
+// runner-up of a low-margin row is accepted outright (Alg. 1), anything else with probability
+// min(1, f(x)/q(x)) (Eq. 1).  Returns the decision code (0 = rejected) and f(x).
+__device__ __forceinline__ int first_try(const mars_row_stat& st, float zx, float qx, int x, float u, float c,
+                                         float& fx) {
+  fx = 0.0f;
+  if (x == st.id2 && st.relax_ok) return MARS_DEC_RELAXED;
+  fx = __builtin_amdgcn_exp2f((zx - st.z1) * c) * (1.0f / st.sum_exp);
+  float acc;
+  if (fx == 0.0f) acc = 0.0f;
+  else if (qx <= 0.0f) acc = 1.0f;
+  else acc = fminf(1.0f, fx / qx);
+  return u < acc ? MARS_DEC_SAMPLED : 0;
+}
+
 // Sum over the work-group.  The caller keeps a barrier between two calls (the exchange that follows
 // every call has one), so the staging array needs none in front of the write.
 template <int NT>
@@ -311,7 +326,7 @@ __device__ __forceinline__ unsigned int exchange_begin(const TailArgs& a, int b,
     if ((threadIdx.x & 1) == 0) sh_part[threadIdx.x >> 1] = v;
   }
   __syncthreads();
-  // (written again only behind the barriers of exchange_end; the same in every lane, and said so: what
+  // (written again only behind the caller's next barrier; the same in every lane, and said so: what
   // is derived from it -- whose slice comes next, its bounds -- then lives in scalar registers)
   return static_cast<unsigned int>(__builtin_amdgcn_readfirstlane(static_cast<int>(*sh_missing)));
 }
@@ -323,13 +338,13 @@ __device__ __forceinline__ void exchange_fill(double* sh_part, int i, double v) 
     sh_part[i] = static_cast<double>(hi) + static_cast<double>(lo);
   }
 }
+// (Behind the barrier that ends exchange_begin, or the one the caller keeps behind its last exchange_fill.
+// Lane i holds work-group i's value; the same tree of additions in every wave of every work-group.  The
+// caller keeps a barrier between this and the next exchange_begin, which writes sh_part again.)
 __device__ __forceinline__ double exchange_end(const TailArgs& a, const double* sh_part) {
   if (a.G == 1) return sh_part[0];
-  __syncthreads();
-  double t = 0.0;
-  for (int i = 0; i < a.G; ++i) t += sh_part[i];
-  __syncthreads();  // sh_part may be rewritten by the next exchange
-  return t;
+  const int lane = threadIdx.x % kWave;
+  return wave_sum(lane < a.G ? sh_part[lane] : 0.0);
 }
 
 // Everything a pass over a row needs to evaluate the current distribution f.
@@ -356,7 +371,10 @@ struct RowView {
   }
 };
 
-constexpr int kPassBatch = 4;  // groups whose loads a thread issues before it starts computing
+// Groups whose loads a thread issues before it starts computing.  (The streamed form runs 1024 threads, so 128
+// registers each; with four groups in flight the kernel needs about 160 and spills, which on the B = 128 chain
+// workload costs 25 us of 105; with two it needs 106 and the sixteen waves keep the memory pipeline as full.)
+constexpr int kPassBatch = 2;
 
 // This work-group's share of Z = sum_v max(0, f(v) - q_k(v)) over groups [g_begin, g_end):
 // q_k dense, or one-hot at token x.  The loads of kPassBatch groups are issued together so
@@ -403,12 +421,7 @@ __device__ __forceinline__ TilePrefix tile_prefix(const double* sh_tile, int n, 
     const int t = lane * per + i;
     if (t < n) p.mine += sh_tile[t];
   }
-  p.incl = p.mine;
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    const double o = __shfl_up(p.incl, d, kWave);
-    if (lane >= d) p.incl += o;
-  }
+  p.incl = wave_prefix_sum(p.mine);
   return p;
 }
 __device__ __forceinline__ double tile_total(const double* sh_tile, int n, int lane) {
@@ -531,6 +544,9 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   __shared__ double sh_tile2[kMaxTiles];         // tile sums of a partner's slice, when they have to be worked out here
   __shared__ unsigned int sh_missing;            // partners of the current exchange that have not arrived
   __shared__ int sh_bad;                         // validation bits of the request
+  __shared__ int32_t sh_first[MARS_MAX_NODES];   // lowest-numbered child of every node (kNoChild: a leaf)
+  __shared__ uint8_t sh_code0[MARS_MAX_NODES];   // decision of every node if it is the first child tested
+  constexpr int32_t kNoChild = 0x7FFFFFFF;
 
   const int G = a.G;
   const int b = blockIdx.x / G, g = blockIdx.x - b * G;
@@ -541,30 +557,49 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   const int tid = threadIdx.x;
   const int wave = tid / kWave, lane = tid % kWave;
   if (tid == 0) sh_bad = 0;
+  for (int i = tid; i < a.N; i += NT) sh_first[i] = kNoChild;
   __syncthreads();
 
   const T* __restrict__ zall = static_cast<const T*>(a.logits) + rd * static_cast<size_t>(V);
   const TQ* __restrict__ qall = a.dprobs ? static_cast<const TQ*>(a.dprobs) + rd * static_cast<size_t>(V) : nullptr;
   const bool dense = qall != nullptr;
 
-  // Prologue, one node per thread: validate tree and token, start the two gathers every
-  // acceptance test needs (logit and draft probability of the node's token in its parent's
-  // row: one round trip for the whole tree instead of one per visited node), and merge the
-  // row partials (sixteen lanes per row) while those loads are in flight.  Every work-group of the
-  // request does this for itself; they produce identical bits, and only the first writes the
-  // caller's outputs.
+  // Prologue, one node per thread.  It is a chain of trips to memory, so every load that depends on
+  // nothing goes out first (tree, tokens, the row's partial results, uniforms); then the two gathers every
+  // acceptance test needs (logit and draft probability of the node's token in its parent's row: one round
+  // trip for the whole tree instead of one per visited node) are started, and the partial results are merged
+  // while those are in flight.  Every work-group of the request does this for itself; they produce
+  // identical bits, and only the first writes the caller's outputs.
+  const int nwords = (N + kWave - 1) / kWave;
   {
     constexpr int kPerThread = (MARS_MAX_NODES + NT - 1) / NT;
     const float theta = a.theta[b];
-    float zx[kPerThread], qx[kPerThread];
+    const bool few = a.splits <= kFewParts;  // one thread merges a row (else sixteen lanes do)
+    const float* __restrict__ ureq = a.u + static_cast<size_t>(bd) * (N + 1);
+    int pr[kPerThread], tk[kPerThread];
+    float zx[kPerThread], qx[kPerThread], uv[kPerThread];
+    Partial pq[kPerThread][kFewParts];
+#pragma unroll
+    for (int t = 0; t < kPerThread; ++t) {
+      const int i = tid + t * NT;
+      pr[t] = -1; tk[t] = 0; uv[t] = 0.0f;
+      if (i < N) {
+        pr[t] = a.par[rd + i];
+        tk[t] = a.tok[rd + i];
+        // (the streamed form is short of registers here: its partial results are requested further down)
+        if (RESIDENT && few) load_partials_of_row(a.partials + (rd + i) * a.splits, a.splits, pq[t]);
+        uv[t] = ureq[i];
+      }
+    }
+    const float u_draw = tid == 0 ? ureq[N] : 0.0f;  // the uniform of the final draw
 #pragma unroll
     for (int t = 0; t < kPerThread; ++t) {
       const int i = tid + t * NT;
       zx[t] = 0.0f; qx[t] = 1.0f;
       if (i < N) {
         const size_t r = rb + i;
-        const int p = a.par[rd + i];
-        const int x = a.tok[rd + i];
+        const int p = pr[t];
+        const int x = tk[t];
         int bad = 0;
         if (i == 0) { if (p != -1) bad = 1; }
         else {
@@ -577,6 +612,7 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
         sh_par[i] = static_cast<int16_t>(p);
         sh_tok[i] = x;
         if (bad) atomicOr(&sh_bad, bad);
+        else if (i > 0) atomicMin(&sh_first[p], i);
         if (g == 0) {
           a.mask[r] = i == 0 ? 1 : 0;
           a.path[r] = -1;
@@ -584,27 +620,58 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
         }
       }
     }
-    for (int i = tid; i <= N; i += NT) sh_u[i] = a.u[static_cast<size_t>(bd) * (N + 1) + i];
-    merge_rows_coop<NT>(a.partials + rd * a.splits, N, a.splits, a.c, a.ind, [&](int) { return theta; },
-                        [&](int row, const mars_row_stat& st) {
-                          sh_st[row] = st;
-                          if (g == 0) {
-                            a.stats_ws[rb + row] = st;
-                            if (a.stats) a.stats[rb + row] = st;
-                          }
-                        });
+    auto emit = [&](int row, const mars_row_stat& st) {
+      sh_st[row] = st;
+      if (g == 0) {
+        a.stats_ws[rb + row] = st;
+        if (a.stats) a.stats[rb + row] = st;
+      }
+    };
+    if (few) {
+#pragma unroll
+      for (int t = 0; t < kPerThread; ++t) {
+        const int i = tid + t * NT;
+        if (i < N) {
+          if (!RESIDENT) load_partials_of_row(a.partials + (rd + i) * a.splits, a.splits, pq[t]);
+          const mars_row_stat st = merge_row_few(pq[t], a.c, a.ind, theta);
+          sh_st[i] = st;
+          if (g == 0) {
+            a.stats_ws[rb + i] = st;
+            if (a.stats) a.stats[rb + i] = st;
+          }
+        }
+      }
+    } else {
+      merge_rows_coop<NT, 2>(a.partials + rd * a.splits, N, a.splits, a.c, a.ind, [&](int) { return theta; }, emit);
+    }
 #pragma unroll
     for (int t = 0; t < kPerThread; ++t) {
       const int i = tid + t * NT;
-      if (i < N) { sh_zx[i] = zx[t]; sh_qx[i] = qx[t]; }
+      if (i < N) { sh_zx[i] = zx[t]; sh_qx[i] = qx[t]; sh_u[i] = uv[t]; }
     }
+    if (tid == 0) sh_u[N] = u_draw;
+    __syncthreads();
+    if (sh_bad != 0) {
+      if (g == 0) write_rejected_request<NT>(a, b, (sh_bad & 1) ? MARS_REQ_BAD_TREE : MARS_REQ_BAD_TOKEN, sh_st[0].id1);
+      return;
+    }
+    // What the walk decides at a node it reaches is, for the node's first child, a function of the inputs
+    // alone: taken here for all nodes at once, so that the walk follows accepted first children at the
+    // price of two LDS reads each.
+#pragma unroll
+    for (int t = 0; t < kPerThread; ++t) {
+      const int i = tid + t * NT;
+      if (i < N) {
+        int code0 = 0;
+        if (i > 0) {
+          float fx;
+          code0 = first_try(sh_st[pr[t]], zx[t], qx[t], tk[t], uv[t], a.c, fx);
+        }
+        sh_code0[i] = static_cast<uint8_t>(code0);
+      }
+    }
+    __syncthreads();
   }
-  __syncthreads();
-  if (sh_bad != 0) {
-    if (g == 0) write_rejected_request<NT>(a, b, (sh_bad & 1) ? MARS_REQ_BAD_TREE : MARS_REQ_BAD_TOKEN, sh_st[0].id1);
-    return;
-  }
-  const int nwords = (N + kWave - 1) / kWave;
 
   const bool vec_ok = (V % 8 == 0) && (reinterpret_cast<uintptr_t>(zall) % 16 == 0) &&
                       (!dense || reinterpret_cast<uintptr_t>(qall) % 16 == 0);
@@ -689,6 +756,21 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   };
 
   for (;;) {
+    {
+      const int k1 = __builtin_amdgcn_readfirstlane(sh_first[cnode]);
+      const int code0 = k1 < N ? __builtin_amdgcn_readfirstlane(static_cast<int>(sh_code0[k1])) : 0;
+      if (code0 != 0) {  // the first child is accepted: nothing else at this node matters
+        if (tid == 0 && g == 0) {
+          a.mask[rb + k1] = 1;
+          a.path[rb + plen] = k1;
+          if (a.dec) a.dec[rb + k1] = static_cast<uint8_t>(code0);
+          if (a.out_tok) a.out_tok[rb + plen] = sh_tok[k1];
+        }
+        cnode = k1;
+        plen += 1;
+        continue;
+      }
+    }
     const mars_row_stat st = sh_st[cnode];
     rv.zrow = zall + static_cast<size_t>(cnode) * V;
     rv.qrow = dense ? qall + static_cast<size_t>(cnode) * V : nullptr;
@@ -721,7 +803,9 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
       // instructions, same bits): no broadcast and no barrier per tested child.
       int code = 0;
       float fx = 0.0f;
-      if (x == st.id2 && st.relax_ok) {
+      if (rv.ch.n == 0) {
+        code = first_try(st, sh_zx[k], sh_qx[k], x, u[k], c, fx);
+      } else if (x == st.id2 && st.relax_ok) {
         code = MARS_DEC_RELAXED;  // runner-up in a low-margin row: accepted outright
       } else {
         const float qx = sh_qx[k];
@@ -919,22 +1003,18 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
         missing &= missing - 1u;
       }
     }
-    total = exchange_end(a, sh_part);
-    // Which work-group's slice holds the target?  The last one with mass if rounding leaves none.
-    const double target = static_cast<double>(u[N]) * total;
-    before = 0.0;
-    owner = -1;
-    int last_mass = -1;
-    for (int i = 0; i < G; ++i) {
-      if (sh_part[i] > 0.0) last_mass = i;
-      if (owner < 0) {
-        if (before + sh_part[i] > target) owner = i; else before += sh_part[i];
-      }
-    }
-    if (owner < 0) {
-      owner = last_mass < 0 ? 0 : last_mass;
-      before = 0.0;
-      for (int i = 0; i < owner; ++i) before += sh_part[i];
+    // Which work-group's slice holds the target?  The last one with mass if rounding leaves none.  Lane i
+    // holds the total of work-group i and the prefix up to it; the grand total is the last prefix.
+    {
+      const double pg = lane < G ? sh_part[lane] : 0.0;
+      const double pincl = wave_prefix_sum(pg);
+      total = lane_value(pincl, kWave - 1);
+      const double target = static_cast<double>(u[N]) * total;
+      const unsigned long long hit = __ballot(lane < G && pincl > target);
+      const unsigned long long mass = __ballot(lane < G && pg > 0.0);
+      if (hit != 0ull) owner = __ffsll(static_cast<long long>(hit)) - 1;
+      else owner = mass != 0ull ? 63 - __clzll(static_cast<long long>(mass)) : 0;
+      before = lane_value(pincl - pg, owner);
     }
     __syncthreads();
     if (!(pending_norm && total <= 0.0)) break;
@@ -1007,12 +1087,7 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
           for (int e = 0; e < 8; ++e) f[e] = 0.0f;
         }
       }
-      double gincl = static_cast<double>(gs);
-#pragma unroll
-      for (int d = 1; d < kWave; d <<= 1) {
-        const double o = __shfl_up(gincl, d, kWave);
-        if (lane >= d) gincl += o;
-      }
+      const double gincl = wave_prefix_sum(static_cast<double>(gs));
       const unsigned long long hit = __ballot(cum + gincl > target);
       // remember the last element with mass, in case rounding leaves no step above the target
       int my_last = -1;

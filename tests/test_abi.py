@@ -115,7 +115,8 @@ def test_host_side_argument_errors_enqueue_nothing(lib):
     assert call_ex(VerifyOptionsStruct(0, -2, 0, 0, None, None, None, None)) == -1
     assert call_ex(VerifyOptionsStruct(0, 1, 0, 0, 0x1000, None, None, None)) == -1  # commit outputs: all or none
     assert call_ex(VerifyOptionsStruct(0, 1, 0, 0, 0x1000, 0x1000, 0x1000, None)) == -1
-    assert call_ex(VerifyOptionsStruct(1, 8, 0, 0, None, None, None, None), wsb=4096) == -3  # the sweep needs more workspace
+    assert lib.mars_workspace_bytes(2, 4, 100) <= 2048 < lib.mars_workspace_bytes_ex(2, 4, 100, 8)
+    assert call_ex(VerifyOptionsStruct(1, 8, 0, 0, None, None, None, None), wsb=2048) == -3  # the sweep needs more workspace
     assert call_ex(VerifyOptionsStruct(0, 1, -5, 0, None, None, None, None)) == -1  # negative spin limit
     assert call_ex(VerifyOptionsStruct(0, 1, 0, 7, None, None, None, None)) == -1   # unknown stages
     assert call_ex(VerifyOptionsStruct(0, 1, 0, -1, None, None, None, None)) == -1
