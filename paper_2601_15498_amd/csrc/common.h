@@ -106,6 +106,9 @@ constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
 constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7 - i inside each group of 8
 constexpr int kDppMirror = 0x140;      // lane i <-> 15 - i inside each row of 16
 
+// The value a given lane holds, the lane being the same for the whole wave (a scalar): a register read,
+// not a trip through the LDS crossbar as a shuffle with a per-lane source would be.
+__device__ __forceinline__ int lane_value(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
 __device__ __forceinline__ float lane_value(float v, int lane) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }

@@ -43,7 +43,7 @@ static int choose_splits(long rows, int V) {
 
 struct Layout {
   int splits, G;
-  size_t partials_off, stats_off, xslots_off, total;
+  size_t partials_off, stats_off, xslots_off, gathered_off, total;
 };
 
 // Work-groups per request in the sampling tail: enough to spread a request's row passes over
@@ -82,8 +82,9 @@ static Layout layout(int B, int N, int V, int K = 1) {
   L.stats_off = align_up(static_cast<size_t>(rows) * L.splits * kPartsPerItem * sizeof(Partial));
   L.G = choose_groups(K * B, V);
   L.xslots_off = L.stats_off + align_up(static_cast<size_t>(K) * rows * sizeof(mars_row_stat));
-  L.total = L.xslots_off +
-            align_up(static_cast<size_t>(K) * B * (N + 2) * 2 * L.G * sizeof(unsigned long long));
+  L.gathered_off = L.xslots_off +
+                   align_up(static_cast<size_t>(K) * B * (N + 2) * 2 * L.G * sizeof(unsigned long long));
+  L.total = L.gathered_off + align_up(static_cast<size_t>(rows) * sizeof(float2));
   return L;
 }
 
@@ -135,6 +136,7 @@ static ClearArgs clear_args(char* ws, const Layout& L, int B, int N, int K) {
   clr.xslots = reinterpret_cast<unsigned long long*>(ws + L.xslots_off);
   clr.N = N; clr.B = B; clr.xwords = 2 * L.G; clr.copies = K;
   clr.counters = nullptr; clr.ncounters = 0;
+  clr.par = nullptr; clr.tok = nullptr; clr.q = nullptr; clr.q_bf16 = 0; clr.gathered = nullptr;
   return clr;
 }
 
@@ -334,6 +336,12 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
   const float c = log2e_over_t(temperature);
 
   ClearArgs clr = clear_args(ws, L, B, N, K);
+  if (sampling) {  // the sampling walk starts from what the row reduction gathers for it
+    clr.par = tree_parent; clr.tok = draft_tokens;
+    clr.q = dense ? draft_probs : nullptr;
+    clr.q_bf16 = draft_dtype == MARS_BF16 ? 1 : 0;
+    clr.gathered = reinterpret_cast<float2*>(ws + L.gathered_off);
+  }
   if (sampling && request_status) {  // the sampling tail only raises a request's status
     clr.counters = reinterpret_cast<unsigned int*>(request_status);
     clr.ncounters = static_cast<long>(K) * B;
@@ -349,6 +357,7 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
   a.theta = theta; a.u = uniforms; a.partials = partials;
   a.stats = stats;
   a.stats_ws = reinterpret_cast<mars_row_stat*>(ws + L.stats_off);
+  a.gathered = reinterpret_cast<const float2*>(ws + L.gathered_off);
   int groups = L.G;
   if (static_cast<long>(K) * B * groups > compute_units()) {
     groups = compute_units() / (K * B);
@@ -383,11 +392,16 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
   const bool resident = slice8 <= kResident * kSamplingThreads;
   const bool qbf = dense && draft_dtype == MARS_BF16;
   const void* kernel;
-#define MARS_PICK(TT, QQ) (resident ? reinterpret_cast<const void*>(&tail_sampling_resident_kernel<TT, QQ>) \
-                                    : reinterpret_cast<const void*>(&tail_sampling_streamed_kernel<TT, QQ>))
+  // groups of eight elements as single aligned loads: whole rows of groups, arrays on 16-byte boundaries
+  const bool vec = (V % 8 == 0) && (reinterpret_cast<uintptr_t>(logits) % 16 == 0) &&
+                   (!dense || reinterpret_cast<uintptr_t>(draft_probs) % 16 == 0);
+#define MARS_PICK2(TT, QQ, VV) (resident ? reinterpret_cast<const void*>(&tail_sampling_resident_kernel<TT, QQ, VV>) \
+                                         : reinterpret_cast<const void*>(&tail_sampling_streamed_kernel<TT, QQ, VV>))
+#define MARS_PICK(TT, QQ) (vec ? MARS_PICK2(TT, QQ, true) : MARS_PICK2(TT, QQ, false))
   if (logits_dtype == MARS_BF16) kernel = qbf ? MARS_PICK(bf16_t, bf16_t) : MARS_PICK(bf16_t, float);
   else kernel = qbf ? MARS_PICK(float, bf16_t) : MARS_PICK(float, float);
 #undef MARS_PICK
+#undef MARS_PICK2
   void* params[] = {&a};
   // With G > 1 the work-groups of a request exchange sums.  The grid never exceeds one work-group
   // per compute unit, so on a GPU that is free to run it all of them are resident together and the
@@ -518,7 +532,7 @@ int mars_lmhead_verify(const void* hidden, const void* weight, int H, const int3
   a.theta = theta; a.u = nullptr; a.partials = partials;
   a.stats = stats;
   a.stats_ws = reinterpret_cast<mars_row_stat*>(ws + L.stats_off);
-  a.G = 1; a.spin_limit = 0; a.xslots = nullptr;
+  a.G = 1; a.spin_limit = 0; a.xslots = nullptr; a.gathered = nullptr;
   a.mask = accept_mask; a.len = accept_len; a.path = path_idx; a.bonus = bonus_token;
   a.dec = decision; a.status = request_status; a.diag = nullptr;
   a.B = K * B; a.Bd = B; a.N = N; a.V = V; a.splits = p.parts; a.c = 0.0f;

@@ -74,12 +74,23 @@ __device__ __forceinline__ unsigned long long lane_value(unsigned long long v, i
   return (static_cast<unsigned long long>(hi) << 32) | lo;
 }
 
-// Memory the row reduction clears on behalf of the kernel that follows it on the stream.
+// What the row reduction does on behalf of the kernel that follows it on the stream: memory it clears,
+// and the gather the sampling walk starts from.
 struct ClearArgs {
   unsigned long long* xslots;  // exchange words of the sampling tail: [copies*B][N+2][xwords]
   int N, B, xwords, copies;
   unsigned int* counters;      // histogram counters (nullptr / 0 = none)
   long ncounters;
+  // Every acceptance test (Eq. 1) needs the logit and the draft probability of a node's token in its
+  // parent's row.  Gathered by the per-request kernel that costs a chain of two trips to memory (tree and
+  // tokens, then the gather) on its critical path; here, the work-group of the parent's row reads the tree
+  // while its first loads are in flight and leaves the pair in `gathered`, at no cost in time.
+  // par == nullptr: not wanted (greedy mode, calls without a tree).
+  const int32_t* par;
+  const int32_t* tok;
+  const void* q;               // draft probabilities [B,N,V] or nullptr (one-hot: the pair's second half is 1)
+  int q_bf16;
+  float2* gathered;            // [B*N]: (logit, draft probability) of node i's token in row par[i]
 };
 
 template <typename T, int EPV, bool SAMPLING>
@@ -121,6 +132,41 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   for (long i = static_cast<long>(item) * kRowThreads + tid; i < clr.ncounters;
        i += static_cast<long>(gridDim.x) * kRowThreads)
     clr.counters[i] = 0u;
+
+  // The children of this row's node, at most kGatherPer per thread: tree and tokens are requested now and
+  // looked at behind the first loads of the stream.
+  constexpr int kGatherPer = (MARS_MAX_NODES + kRowThreads - 1) / kRowThreads;
+  const bool gather = clr.par != nullptr && split == 0;
+  const int gnode = row % clr.N;
+  const size_t greq = static_cast<size_t>(row - gnode);  // first row of the request
+  int gpar[kGatherPer], gtok[kGatherPer];
+  float2 gval[kGatherPer];
+#pragma unroll
+  for (int j = 0; j < kGatherPer; ++j) {
+    const int i = tid + j * kRowThreads;
+    gpar[j] = -2; gtok[j] = -1;
+    if (gather && i > gnode && i < clr.N) { gpar[j] = clr.par[greq + i]; gtok[j] = clr.tok[greq + i]; }
+  }
+  auto gather_issue = [&]() {
+#pragma unroll
+    for (int j = 0; j < kGatherPer; ++j) {
+      gval[j] = make_float2(0.0f, 1.0f);
+      if (gpar[j] == gnode && static_cast<unsigned int>(gtok[j]) < static_cast<unsigned int>(V)) {
+        gval[j].x = widen(rowp[gtok[j]]);
+        if (clr.q) {
+          const size_t at = static_cast<size_t>(row) * static_cast<size_t>(V) + gtok[j];
+          gval[j].y = clr.q_bf16 ? widen(static_cast<const bf16_t*>(clr.q)[at]) : static_cast<const float*>(clr.q)[at];
+        }
+      } else {
+        gpar[j] = -2;
+      }
+    }
+  };
+  auto gather_store = [&]() {
+#pragma unroll
+    for (int j = 0; j < kGatherPer; ++j)
+      if (gpar[j] == gnode) clr.gathered[greq + tid + j * kRowThreads] = gval[j];
+  };
 
   float m1 = neg_inf(), m2 = neg_inf();  // best and second-best batch maximum of this lane
   int b1 = -1, b2 = -1;                  // the (distinct) batches they belong to
@@ -227,6 +273,7 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   if (nfull > 2) {
     load_full(bufA, 0);
     __syncthreads();
+    gather_issue();
     for (; k + 2 < nfull; k += 2) {
       load_full(bufB, k + 1);
       process(bufA, k);
@@ -237,12 +284,14 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
     ++k;
   } else {
     __syncthreads();
+    gather_issue();
   }
 #pragma unroll 1
   for (; k < nb; ++k) {
     load_tail(bufB, k);
     process(bufB, k);
   }
+  gather_store();
 
   // ------------------------------------------------------------------ per-wave epilogue
   const int wave = tid / kWave, lane = tid % kWave;

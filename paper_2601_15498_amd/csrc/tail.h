@@ -28,6 +28,7 @@ struct TailArgs {
   const float* theta;
   const float* u;
   const Partial* partials;
+  const float2* gathered;   // sampling mode: (logit, draft probability) of every node's token in its parent's row
   mars_row_stat* stats;     // optional caller's table [B*N]
   mars_row_stat* stats_ws;  // [B*N] in the workspace: the table the tail itself reads
   uint8_t* mask;
@@ -426,7 +427,7 @@ __device__ __forceinline__ TilePrefix tile_prefix(const double* sh_tile, int n, 
 }
 __device__ __forceinline__ double tile_total(const double* sh_tile, int n, int lane) {
   const int per = (n + kWave - 1) / kWave;
-  return __shfl(tile_prefix(sh_tile, n, per, lane).incl, kWave - 1, kWave);
+  return lane_value(tile_prefix(sh_tile, n, per, lane).incl, kWave - 1);
 }
 // The first tile whose inclusive prefix (on top of `before`) exceeds target, and the prefix in
 // front of it; when rounding leaves none, the last tile with mass (tile 0 if there is none).
@@ -441,7 +442,7 @@ __device__ __forceinline__ void tile_find(const double* sh_tile, int n, int lane
     if (t < n && sh_tile[t] > 0.0) my_last = t;
   }
   const unsigned long long has = __ballot(my_last >= 0);
-  const int last_tile = has != 0ull ? __shfl(my_last, 63 - __clzll(static_cast<long long>(has)), kWave) : 0;
+  const int last_tile = has != 0ull ? lane_value(my_last, 63 - __clzll(static_cast<long long>(has))) : 0;
   const unsigned long long hit = __ballot(before + p.incl > target);
   int found = -1;
   double front = 0.0;
@@ -456,8 +457,8 @@ __device__ __forceinline__ void tile_find(const double* sh_tile, int n, int lane
         }
       }
     }
-    found = __shfl(found, hl, kWave);
-    front = __shfl(front, hl, kWave);
+    found = lane_value(found, hl);
+    front = lane_value(front, hl);
   }
   if (found < 0) {  // rounding: the last tile with mass, with the prefix in front of it
     found = last_tile;
@@ -467,7 +468,7 @@ __device__ __forceinline__ void tile_find(const double* sh_tile, int n, int lane
       const int t = lane * per + i;
       if (t < found) run += sh_tile[t];
     }
-    front = __shfl(run, ol, kWave);
+    front = lane_value(run, ol);
   }
   tile = found;
   cum = front;
@@ -522,11 +523,15 @@ __device__ __forceinline__ int resident_tiles_from_memory(const RowView<T, TQ>& 
 
 constexpr float kClosedFormMinNorm = 0.1f; // one-hot residual: Z = 1 - f(x) is used when at least this
 constexpr int kResident = 3;               // groups of eight elements a thread can keep in registers
+constexpr int kCodeWarmBytes = 40 * 1024;  // of the sampling tail's own code, read ahead as data (every instantiation is longer)
 
 // RESIDENT: every slice is at most kResident groups per thread (decided by the host from G and V).
 // (At most 184 registers: a work-group of the row reduction of another call -- two waves per SIMD at 72 -- then
 // still fits on a compute unit beside a resident tail's two at 184, and calls on two streams overlap.)
-template <typename T, typename TQ, bool RESIDENT>
+// VEC: every group of eight elements is one aligned 16-byte (or 32-byte) load -- the host checks V % 8 and
+// the alignment of the arrays.  The form that checks every element against the end of the row costs some
+// eighty comparisons and as many scalar registers before the walk starts, on the critical path of every call.
+template <typename T, typename TQ, bool RESIDENT, bool VEC>
 __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   constexpr int NT = RESIDENT ? kSamplingThreads : kStreamingThreads;
   constexpr int NW = NT / kWave;
@@ -556,6 +561,17 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   const size_t rd = static_cast<size_t>(bd) * N;
   const int tid = threadIdx.x;
   const int wave = tid / kWave, lane = tid % kWave;
+  // This kernel runs its ~48 KB of code once, behind a row reduction that has just streamed hundreds of
+  // megabytes through the L2: every jump into code not yet fetched is a trip to HBM.  The last wave, which
+  // has nothing to do in the prologue, reads the first kCodeWarmBytes of the kernel as data, so that the
+  // instruction fetches that follow find them in the L2.
+  int warm = 0;
+  if (wave == NW - 1) {
+    const char* pc = reinterpret_cast<const char*>(__builtin_amdgcn_s_getpc());
+#pragma unroll
+    for (int off = 0; off < kCodeWarmBytes; off += kWave * 128)
+      warm += *reinterpret_cast<const int*>(pc + off + lane * 128);
+  }
   if (tid == 0) sh_bad = 0;
   for (int i = tid; i < a.N; i += NT) sh_first[i] = kNoChild;
   __syncthreads();
@@ -564,12 +580,11 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   const TQ* __restrict__ qall = a.dprobs ? static_cast<const TQ*>(a.dprobs) + rd * static_cast<size_t>(V) : nullptr;
   const bool dense = qall != nullptr;
 
-  // Prologue, one node per thread.  It is a chain of trips to memory, so every load that depends on
-  // nothing goes out first (tree, tokens, the row's partial results, uniforms); then the two gathers every
-  // acceptance test needs (logit and draft probability of the node's token in its parent's row: one round
-  // trip for the whole tree instead of one per visited node) are started, and the partial results are merged
-  // while those are in flight.  Every work-group of the request does this for itself; they produce
-  // identical bits, and only the first writes the caller's outputs.
+  // Prologue, one node per thread.  It is one trip to memory: tree, tokens, the row's partial results,
+  // uniforms, and the logit and draft probability of every node's token in its parent's row (which every
+  // acceptance test needs, and which the row reduction of this call has gathered) all go out together.
+  // Every work-group of the request does this for itself; they produce identical bits, and only the first
+  // writes the caller's outputs.
   const int nwords = (N + kWave - 1) / kWave;
   {
     constexpr int kPerThread = (MARS_MAX_NODES + NT - 1) / NT;
@@ -577,25 +592,26 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
     const bool few = a.splits <= kFewParts;  // one thread merges a row (else sixteen lanes do)
     const float* __restrict__ ureq = a.u + static_cast<size_t>(bd) * (N + 1);
     int pr[kPerThread], tk[kPerThread];
-    float zx[kPerThread], qx[kPerThread], uv[kPerThread];
+    float zx[kPerThread], qx[kPerThread], uv[kPerThread];  // (zx, qx: gathered by the row reduction of this call)
     Partial pq[kPerThread][kFewParts];
 #pragma unroll
     for (int t = 0; t < kPerThread; ++t) {
       const int i = tid + t * NT;
-      pr[t] = -1; tk[t] = 0; uv[t] = 0.0f;
+      pr[t] = -1; tk[t] = 0; uv[t] = 0.0f; zx[t] = 0.0f; qx[t] = 1.0f;
       if (i < N) {
         pr[t] = a.par[rd + i];
         tk[t] = a.tok[rd + i];
         // (the streamed form is short of registers here: its partial results are requested further down)
         if (RESIDENT && few) load_partials_of_row(a.partials + (rd + i) * a.splits, a.splits, pq[t]);
         uv[t] = ureq[i];
+        const float2 zq = a.gathered[rd + i];
+        zx[t] = zq.x; qx[t] = zq.y;
       }
     }
     const float u_draw = tid == 0 ? ureq[N] : 0.0f;  // the uniform of the final draw
 #pragma unroll
     for (int t = 0; t < kPerThread; ++t) {
       const int i = tid + t * NT;
-      zx[t] = 0.0f; qx[t] = 1.0f;
       if (i < N) {
         const size_t r = rb + i;
         const int p = pr[t];
@@ -606,9 +622,7 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
           if (p < 0 || p >= i) bad |= 1;
           if (x < 0 || x >= V) bad |= 2;
         }
-        const size_t at = (i > 0 && bad == 0) ? static_cast<size_t>(p) * V + x : 0;
-        zx[t] = widen(zall[at]);                 // consumed after the merge below
-        if (dense) qx[t] = widen(qall[at]);
+        if (i == 0 || bad != 0) { zx[t] = 0.0f; qx[t] = 1.0f; }  // (nothing was gathered for these)
         sh_par[i] = static_cast<int16_t>(p);
         sh_tok[i] = x;
         if (bad) atomicOr(&sh_bad, bad);
@@ -650,6 +664,7 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
       if (i < N) { sh_zx[i] = zx[t]; sh_qx[i] = qx[t]; sh_u[i] = uv[t]; }
     }
     if (tid == 0) sh_u[N] = u_draw;
+    if (warm == 0x5EEDC0DE && N < 0) sh_bad = warm;  // (never: keeps the reads above alive)
     __syncthreads();
     if (sh_bad != 0) {
       if (g == 0) write_rejected_request<NT>(a, b, (sh_bad & 1) ? MARS_REQ_BAD_TREE : MARS_REQ_BAD_TOKEN, sh_st[0].id1);
@@ -673,8 +688,7 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
     __syncthreads();
   }
 
-  const bool vec_ok = (V % 8 == 0) && (reinterpret_cast<uintptr_t>(zall) % 16 == 0) &&
-                      (!dense || reinterpret_cast<uintptr_t>(qall) % 16 == 0);
+  constexpr bool vec_ok = VEC;
   const int ngroups = (V + 7) / 8;
   // This work-group's slice of the vocabulary, in groups of eight elements (a multiple of 64
   // groups, so that the slices are made of whole wave steps).
@@ -1096,16 +1110,16 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
       const unsigned long long has = __ballot(my_last >= 0);
       if (has != 0ull) {
         const int hl = 63 - __clzll(static_cast<long long>(has));
-        const int le = __shfl(my_last, hl, kWave);
+        const int le = lane_value(my_last, hl);
         float fv = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) if (e == my_last) fv = f[e];
-        last_pos_f = __shfl(fv, hl, kWave);
-        last_pos_v = __shfl(gi, hl, kWave) * 8 + le;
+        last_pos_f = lane_value(fv, hl);
+        last_pos_v = lane_value(gi, hl) * 8 + le;
       }
       if (hit != 0ull) {
         const int hl = __ffsll(static_cast<long long>(hit)) - 1;
-        double run = cum + __shfl(gincl - static_cast<double>(gs), hl, kWave);
+        double run = cum + lane_value(gincl - static_cast<double>(gs), hl);
         int pe = -1;
         float pf = 0.0f;
         if (lane == hl) {
@@ -1117,16 +1131,16 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
             }
           }
         }
-        pe = __shfl(pe, hl, kWave);
+        pe = lane_value(pe, hl);
         if (pe >= 0) {
-          pick_f = __shfl(pf, hl, kWave);
-          pick = __shfl(gi, hl, kWave) * 8 + pe;
+          pick_f = lane_value(pf, hl);
+          pick = lane_value(gi, hl) * 8 + pe;
         } else {  // rounding left no step above the target inside the lane: last element with mass
           pick = last_pos_v; pick_f = last_pos_f;
           break;
         }
       } else {
-        cum += __shfl(gincl, kWave - 1, kWave);
+        cum += lane_value(gincl, kWave - 1);
       }
     }
     if (pick < 0) { pick = last_pos_v; pick_f = last_pos_f; }
@@ -1146,13 +1160,13 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   }
 }
 
-template <typename T, typename TQ>
+template <typename T, typename TQ, bool VEC>
 __global__ __launch_bounds__(kSamplingThreads) void tail_sampling_resident_kernel(TailArgs a) {
-  tail_sampling_body<T, TQ, true>(a);
+  tail_sampling_body<T, TQ, true, VEC>(a);
 }
-template <typename T, typename TQ>
+template <typename T, typename TQ, bool VEC>
 __global__ __launch_bounds__(kStreamingThreads) void tail_sampling_streamed_kernel(TailArgs a) {
-  tail_sampling_body<T, TQ, false>(a);
+  tail_sampling_body<T, TQ, false, VEC>(a);
 }
 
 // ---------------------------------------------------------------- cache rows that stay
