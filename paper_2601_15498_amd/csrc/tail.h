@@ -523,7 +523,6 @@ __device__ __forceinline__ int resident_tiles_from_memory(const RowView<T, TQ>& 
 
 constexpr float kClosedFormMinNorm = 0.1f; // one-hot residual: Z = 1 - f(x) is used when at least this
 constexpr int kResident = 3;               // groups of eight elements a thread can keep in registers
-constexpr int kCodeWarmBytes = 40 * 1024;  // of the sampling tail's own code, read ahead as data (every instantiation is longer)
 
 // RESIDENT: every slice is at most kResident groups per thread (decided by the host from G and V).
 // (At most 184 registers: a work-group of the row reduction of another call -- two waves per SIMD at 72 -- then
@@ -561,17 +560,6 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   const size_t rd = static_cast<size_t>(bd) * N;
   const int tid = threadIdx.x;
   const int wave = tid / kWave, lane = tid % kWave;
-  // This kernel runs its ~48 KB of code once, behind a row reduction that has just streamed hundreds of
-  // megabytes through the L2: every jump into code not yet fetched is a trip to HBM.  The last wave, which
-  // has nothing to do in the prologue, reads the first kCodeWarmBytes of the kernel as data, so that the
-  // instruction fetches that follow find them in the L2.
-  int warm = 0;
-  if (wave == NW - 1) {
-    const char* pc = reinterpret_cast<const char*>(__builtin_amdgcn_s_getpc());
-#pragma unroll
-    for (int off = 0; off < kCodeWarmBytes; off += kWave * 128)
-      warm += *reinterpret_cast<const int*>(pc + off + lane * 128);
-  }
   if (tid == 0) sh_bad = 0;
   for (int i = tid; i < a.N; i += NT) sh_first[i] = kNoChild;
   __syncthreads();
@@ -664,7 +652,6 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
       if (i < N) { sh_zx[i] = zx[t]; sh_qx[i] = qx[t]; sh_u[i] = uv[t]; }
     }
     if (tid == 0) sh_u[N] = u_draw;
-    if (warm == 0x5EEDC0DE && N < 0) sh_bad = warm;  // (never: keeps the reads above alive)
     __syncthreads();
     if (sh_bad != 0) {
       if (g == 0) write_rejected_request<NT>(a, b, (sh_bad & 1) ? MARS_REQ_BAD_TREE : MARS_REQ_BAD_TOKEN, sh_st[0].id1);
