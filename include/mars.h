@@ -231,8 +231,10 @@ int mars_verify(const void* logits, int logits_dtype,
  *                 work, and to tests of that path (1 = never wait).
  *   stages        which part of the pass the call enqueues: 0 or MARS_STAGE_ROWS | MARS_STAGE_REQUESTS = all of
  *                 it; MARS_STAGE_ROWS = the row reduction only (it also clears what the second part
- *                 accumulates into); MARS_STAGE_REQUESTS = the per-request part only, on a workspace the
- *                 first part has filled (same arguments in both calls).  Splitting a pass lets a caller
+ *                 accumulates into and, in sampling mode, gathers the logit and draft probability of
+ *                 every node's token for it); MARS_STAGE_REQUESTS = the per-request part only, on a
+ *                 workspace that the first part of a mars_verify_ex call with the same arguments has
+ *                 filled (mars_row_reduce does not: it knows no tree).  Splitting a pass lets a caller
  *                 that overlaps passes on several streams put its own events between the parts: the
  *                 per-request part of a sampling-mode pass holds up to one work-group per compute unit
  *                 and is quickest when all of them are resident together, so the per-request parts of

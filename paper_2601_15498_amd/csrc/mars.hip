@@ -406,7 +406,7 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
   // With G > 1 the work-groups of a request exchange sums.  The grid never exceeds one work-group
   // per compute unit, so on a GPU that is free to run it all of them are resident together and the
   // exchanges take a couple of microseconds; when other work keeps some of them waiting for a
-  // compute unit, those that run work out the missing sums themselves (tail.h: exchange_sum) --
+  // compute unit, those that run work out the missing sums themselves (tail.h: exchange_begin) --
   // slower, same bits, and no work-group ever depends on another one being there.
   if (hipLaunchKernel(kernel, dim3(static_cast<unsigned int>(K * B) * a.G), dim3(resident ? kSamplingThreads : kStreamingThreads), params, 0,
                       stream) !=
