@@ -80,6 +80,8 @@ WORKLOADS = {
     "lmhead": dict(cfg=None, what="greedy verification from hidden states: B=16, 60-node tree per request, H=4096, "
                                   "V=151936, bf16 hidden states and LM-head weight, theta=0.9; logits formed, reduced "
                                   "and dropped inside one kernel"),
+    "lmhead_sampling": dict(cfg=None, what="sampling verification (T=0.7, dense fp32 q) from hidden states: B=16, 60-node "
+                            "tree per request, H=4096, V=151936; the logits are written once by the fused kernel"),
 }
 
 
@@ -168,19 +170,31 @@ def main_lmhead(args) -> int:
     dev = torch.device("cuda:0")
     spec = dict(LMHEAD_CONFIGS["headline"])
     name = spec.pop("name")
+    sampling = args.workload == "lmhead_sampling"
     t_gen = time.perf_counter()
-    w = make_lmhead_workload(name, seed=2, **spec)
+    if sampling:   # lattice inputs (exact fp32 sums), dense draft distribution
+        w = make_lmhead_workload(name, seed=2, lattice=True, temperature=0.7, dense_q=True, **spec)
+    else:
+        w = make_lmhead_workload(name, seed=2, **spec)
     t_gen = time.perf_counter() - t_gen
     B, N, H, V = w.B, w.N, w.H, w.V
     rows = B * N
     d = dict(h=torch.from_numpy(w.hidden).to(dev), w=torch.from_numpy(w.weight).to(dev),
              tok=torch.from_numpy(w.draft_tokens).to(dev), par=torch.from_numpy(w.tree_parent).to(dev),
              th=torch.from_numpy(np.ascontiguousarray(w.theta, np.float32)).to(dev))
-    out = M.VerifyOutputs(B, N, dev, want_diag=False)
+    out = M.VerifyOutputs(B, N, dev, want_diag=sampling)
     ws = torch.empty(M.mars_lmhead_workspace_bytes(B, N, V, H), dtype=torch.uint8, device=dev)
+    if sampling:
+        d["u"] = torch.from_numpy(w.uniforms).to(dev)
+        d["q"] = torch.from_numpy(w.draft_probs).to(dev)
+        logits_out = torch.empty((B, N, V), dtype=torch.uint16, device=dev)
 
     def step(stages=0):
-        M.mars_lmhead_verify(d["h"], d["w"], d["tok"], d["par"], d["th"], out, ws, stages=stages)
+        if sampling:
+            M.mars_lmhead_verify_sampling(d["h"], d["w"], d["tok"], d["par"], d["th"], w.temperature, d["u"], d["q"],
+                                          logits_out, out, ws, stages=stages)
+        else:
+            M.mars_lmhead_verify(d["h"], d["w"], d["tok"], d["par"], d["th"], out, ws, stages=stages)
 
     def timed(n):
         torch.cuda.synchronize()
@@ -221,20 +235,35 @@ def main_lmhead(args) -> int:
     e1.record()
     torch.cuda.synchronize()
     gemm_us = e0.elapsed_time(e1) / n_mm * 1e3
+    unfused_pass_us = None
+    if sampling:   # what follows the library GEMM in an unfused pipeline: the pass over the stored logits
+        out2 = M.VerifyOutputs(B, N, dev)
+        ws2 = M.alloc_workspace(B, N, V)
+        for _ in range(3):
+            M.mars_verify(logits_out, d["tok"], d["par"], d["th"], w.temperature, d["u"], d["q"], out2, ws2)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(n_mm):
+            M.mars_verify(logits_out, d["tok"], d["par"], d["th"], w.temperature, d["u"], d["q"], out2, ws2)
+        e1.record()
+        torch.cuda.synchronize()
+        unfused_pass_us = e0.elapsed_time(e1) / n_mm * 1e3
     result = {
-        "metric": "rows/s + achieved bf16 MFMA TFLOP/s vs peak, workload 'lmhead'",
+        "metric": f"rows/s + achieved bf16 MFMA TFLOP/s vs peak, workload '{args.workload}'",
         "value": rows * args.steps / elapsed, "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": WORKLOADS["lmhead"]["what"], "B": B, "N": N, "H": H, "V": V, "rows_per_step": rows,
+        "config": {"workload": WORKLOADS[args.workload]["what"], "B": B, "N": N, "H": H, "V": V, "rows_per_step": rows,
                    "streams": 1, "mean_tau": tau, "requests_with_nonzero_status": statuses,
                    "weight_bytes": V * H * 2, "weight_stream_GBps": V * H * 2 / (k_ms * 1e-3) / 1e9,
-                   "library_gemm_us": gemm_us,
+                   "library_gemm_us": gemm_us, "unfused_pass_behind_the_gemm_us": unfused_pass_us,
+                   "logits_bytes_written": rows * V * 2 if sampling else 0,
                    "input_generation_s": round(t_gen, 1)},
-        "roofline": {"bound": "mfma", "kernel": "lmhead_reduce_kernel<192>", "achieved": achieved,
+        "roofline": {"bound": "mfma", "kernel": "lmhead_reduce_kernel<192, %s>" % ("sampling" if sampling else "greedy"), "achieved": achieved,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": measured_lmhead_traffic(), "algorithmic_flops_per_launch": flops,
-                     "algorithmic_bytes_per_launch": V * H * 2 + rows * H * 2, "avg_launch_us": k_ms * 1e3},
+                     "traffic": None if sampling else measured_lmhead_traffic(), "algorithmic_flops_per_launch": flops,
+                     "algorithmic_bytes_per_launch": V * H * 2 + rows * H * 2 + (rows * V * 2 if sampling else 0),
+                     "avg_launch_us": k_ms * 1e3},
     }
     if not args.no_cpu_baseline:
         from threadpoolctl import threadpool_info
@@ -244,8 +273,13 @@ def main_lmhead(args) -> int:
         reps, cpu_s = 0, 0.0
         while reps < 2 or (cpu_s < 10.0 and reps < 20):
             t = time.perf_counter()
-            lmhead_ref.lmhead_verify(w.hidden[:sample], w.weight, w.draft_tokens[:sample], w.tree_parent[:sample],
-                                     w.theta[:sample])
+            if sampling:
+                lmhead_ref.lmhead_verify_sampling(w.hidden[:sample], w.weight, w.draft_tokens[:sample],
+                                                  w.tree_parent[:sample], w.theta[:sample], w.temperature,
+                                                  w.uniforms[:sample], w.draft_probs[:sample])
+            else:
+                lmhead_ref.lmhead_verify(w.hidden[:sample], w.weight, w.draft_tokens[:sample], w.tree_parent[:sample],
+                                         w.theta[:sample])
             cpu_s += time.perf_counter() - t
             reps += 1
         threads = max([int(i.get("num_threads", 1)) for i in threadpool_info()] or [1])
@@ -280,7 +314,7 @@ def main() -> int:
         args.steps = WORKLOADS[args.workload].get("steps", 400)
     if args.warmup is None:
         args.warmup = WORKLOADS[args.workload].get("warmup", 40)
-    if args.workload == "lmhead":
+    if args.workload in ("lmhead", "lmhead_sampling"):
         return main_lmhead(args)
 
     import numpy as np

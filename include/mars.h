@@ -384,6 +384,34 @@ int mars_lmhead_verify(const void* hidden, const void* weight, int H,
                        void* workspace, size_t workspace_bytes, void* hip_stream,
                        const mars_verify_options* options);
 
+/*
+ * Sampling-mode verification straight from the last hidden states: Eq. 2 followed by Eq. 3 in one kernel.
+ * The LM-head product runs on the matrix cores as in mars_lmhead_verify; the logits (fp32-accumulated
+ * products rounded once to bf16) are written to `logits_out` once, from the registers they are formed in
+ * -- under sampling the residual passes of the walk read rows of them again (Sec. 2.3), so they have to
+ * exist -- and each row's top-2 and sum of exponentials are taken on the way: the logits are not read
+ * back for the statistics.  Everything behind that is the sampling walk of mars_verify_ex on `logits_out`.
+ *
+ *   hidden, weight, H   as for mars_lmhead_verify.
+ *   draft_probs, draft_dtype, temperature (> 0), uniforms   as for mars_verify.
+ *   V                   a multiple of 8.
+ *   logits_out          device out, [B,N,V] bf16, 16-byte aligned, caller-owned.
+ *   outputs, options    as for mars_verify_ex (request_status, decision, stats, diag optional).
+ *   workspace           device, 256-byte aligned, >= mars_lmhead_workspace_bytes(B,N,V,H,n_theta).
+ * Returns MARS_OK or a negative code (MARS_ERR_ARG also for temperature <= 0: use mars_lmhead_verify).
+ * Error behaviour and overlap of calls as for mars_lmhead_verify.
+ */
+int mars_lmhead_verify_sampling(const void* hidden, const void* weight, int H,
+                                const int32_t* draft_tokens, const int32_t* tree_parent,
+                                const void* draft_probs, int draft_dtype,
+                                const float* theta, float temperature, const float* uniforms,
+                                int B, int N, int V, void* logits_out,
+                                uint8_t* accept_mask, int32_t* accept_len, int32_t* path_idx,
+                                int32_t* bonus_token, uint8_t* decision, int32_t* request_status,
+                                mars_row_stat* stats, mars_req_diag* diag,
+                                void* workspace, size_t workspace_bytes, void* hip_stream,
+                                const mars_verify_options* options);
+
 #ifdef __cplusplus
 }
 #endif

@@ -14,6 +14,17 @@ Recipe:
   top entry of its parent's row w.p. 0.6, the planted runner-up w.p. 0.25, otherwise uniform over
   the vocabulary (always uniform under an unplanted parent); siblings get distinct tokens.
 
+With ``lattice=True`` every hidden state is a multiple of 2^-5 (below 8 in magnitude) and every weight a
+multiple of 2^-10 (below 1/4): both are still bf16 values, every product is a multiple of 2^-15, and as long
+as the sum of the products' magnitudes of a (row, vocabulary entry) pair stays below 512 -- it is about 125
+for the background and at most 30 for a planted entry; a test checks it -- every partial sum, in any order
+of addition, is a multiple of 2^-15 below 2^9 and therefore exact in fp32.  An fp32-accumulating LM head
+then produces the exact product, and its bf16 rounding is that of the exact value: such workloads serve
+paths in which every logit matters (sampling: Eq. 3 runs over the whole row), where keeping a few deciding
+entries clear of the rounding boundaries is not enough.  Sampling-mode workloads also carry uniforms
+[B,N+1] and, optionally, a dense fp32 draft distribution [B,N,V] (softmax of seeded N(0, 2^2) noise,
+independent of the target: no logit is formed here).
+
 ``redraw_rows`` draws chosen rows again (hidden state and planted weight rows, same ids) from seeds
 of their own; a test uses it to move rows whose exact logits sit too close to a rounding boundary
 or to the threshold.  No logit is computed in this module.
@@ -42,6 +53,9 @@ class LmHeadWorkload:
     tree_parent: np.ndarray   # [B,N] int32
     planted: np.ndarray       # [B,N,2] int32: planted (top, runner-up) ids of the row, -1 if none
     meta: dict = field(default_factory=dict)
+    temperature: float = 0.0
+    uniforms: np.ndarray = None     # [B,N+1] fp32 (sampling-mode workloads)
+    draft_probs: np.ndarray = None  # [B,N,V] fp32 or None (one-hot draft distribution)
 
     @property
     def rows(self) -> int:
@@ -50,6 +64,8 @@ class LmHeadWorkload:
     def _draw_row(self, row: int, round_: int) -> None:
         rng = _rng(self.meta["seed"], 7100 + round_, row)
         h32 = rng.standard_normal(self.H, dtype=np.float32)
+        if self.meta.get("lattice"):
+            h32 = _to_lattice(h32, 5, 7.96875)
         hb = f32_to_bf16_bits(h32)
         self.hidden.reshape(self.rows, self.H)[row] = hb
         ids = self.planted.reshape(self.rows, 2)[row]
@@ -59,8 +75,11 @@ class LmHeadWorkload:
         t = rng.uniform(20.0, 30.0)
         r = rng.uniform(*self.meta["r_range"])
         unit = h / float(h @ h)
-        self.weight[ids[0]] = f32_to_bf16_bits((t * unit).astype(np.float32))
-        self.weight[ids[1]] = f32_to_bf16_bits((r * t * unit).astype(np.float32))
+        top, second = (t * unit).astype(np.float32), (r * t * unit).astype(np.float32)
+        if self.meta.get("lattice"):
+            top, second = _to_lattice(top, 10, 0.2490234375), _to_lattice(second, 10, 0.2490234375)
+        self.weight[ids[0]] = f32_to_bf16_bits(top)
+        self.weight[ids[1]] = f32_to_bf16_bits(second)
 
     def redraw_rows(self, rows: Sequence[int], round_: int) -> None:
         """Draw the given flat rows (b*N + i) again; ``round_`` >= 1 selects the seed."""
@@ -69,9 +88,16 @@ class LmHeadWorkload:
             self._draw_row(int(row), int(round_))
 
 
+def _to_lattice(x: np.ndarray, bits: int, limit: float) -> np.ndarray:
+    """Nearest multiple of 2^-bits, clipped to +-limit (itself such a multiple with at most 8 significant bits)."""
+    s = np.float32(2.0 ** bits)
+    return np.clip(np.rint(x * s) / s, -limit, limit).astype(np.float32)
+
+
 def make_lmhead_workload(name: str, *, B: int, N: int, H: int, V: int, tree: dict, plant_frac: float = 0.6,
                          r_range: Sequence[float] = (0.80, 1.00), theta_choices: Sequence[float] = (0.9,),
-                         seed: int = 0) -> LmHeadWorkload:
+                         seed: int = 0, lattice: bool = False, temperature: float = 0.0,
+                         dense_q: bool = False) -> LmHeadWorkload:
     rows = B * N
     if V < 2 * rows + 2:
         raise ValueError("every row needs two vocabulary entries of its own: V >= 2*B*N + 2")
@@ -84,7 +110,8 @@ def make_lmhead_workload(name: str, *, B: int, N: int, H: int, V: int, tree: dic
     step = max(1, (1 << 22) // H)
     for c, v0 in enumerate(range(0, V, step)):
         v1 = min(V, v0 + step)
-        weight[v0:v1] = f32_to_bf16_bits(_rng(seed, 7000, c).standard_normal((v1 - v0, H), dtype=np.float32) * scale)
+        blk = _rng(seed, 7000, c).standard_normal((v1 - v0, H), dtype=np.float32) * scale
+        weight[v0:v1] = f32_to_bf16_bits(_to_lattice(blk, 10, 0.2490234375) if lattice else blk)
 
     perm = _rng(seed, 7200, 0).permutation(V)[:2 * rows].astype(np.int32).reshape(rows, 2)
     is_planted = _rng(seed, 7201, 0).random(rows) < plant_frac
@@ -118,9 +145,20 @@ def make_lmhead_workload(name: str, *, B: int, N: int, H: int, V: int, tree: dic
     w = LmHeadWorkload(name=name, B=B, N=N, H=H, V=V, theta=theta,
                        hidden=np.empty((B, N, H), dtype=np.uint16), weight=weight, draft_tokens=tokens,
                        tree_parent=parents, planted=planted,
-                       meta=dict(seed=seed, tree=tree, plant_frac=plant_frac, r_range=tuple(r_range)))
+                       meta=dict(seed=seed, tree=tree, plant_frac=plant_frac, r_range=tuple(r_range), lattice=lattice),
+                       temperature=float(temperature))
     for row in range(rows):
         w._draw_row(row, 0)
+    if temperature > 0.0:
+        w.uniforms = np.stack([_rng(seed, 4000, b).random(N + 1, dtype=np.float32) for b in range(B)])
+        if dense_q:
+            q = np.empty((B, N, V), dtype=np.float32)
+            for b in range(B):
+                x = _rng(seed, 5000, b).standard_normal((N, V), dtype=np.float32) * np.float32(2.0)
+                x -= x.max(axis=1, keepdims=True)
+                np.exp(x, out=x)
+                q[b] = x / x.sum(axis=1, keepdims=True, dtype=np.float64).astype(np.float32)
+            w.draft_probs = q
     return w
 
 

@@ -80,6 +80,25 @@ def lmhead_verify(hidden_bits, weight_bits, draft_tokens, tree_parent, theta, in
     return out
 
 
+def lmhead_verify_sampling(hidden_bits, weight_bits, draft_tokens, tree_parent, theta, temperature, uniforms,
+                           draft_probs=None, indicator=mars_ref.IND_LOGIT_RATIO, exact=None):
+    """Sampling-mode verification (Eq. 1 with the relaxed runner-up, residual resampling: ``mars_ref.verify`` at
+    temperature > 0) on the logits of Eq. 2 as defined above: the exact product rounded once to bf16.  Eq. 3
+    runs over the whole row, so every logit counts: an fp32-accumulating implementation agrees with this
+    only where its sums are exact (lattice inputs) or where no entry sits on a rounding boundary.
+    Returns the dict of ``mars_ref.verify`` plus ``logits_bits`` [B,N,V] and ``exact`` [B*N,V]."""
+    B, N, H = hidden_bits.shape
+    V = weight_bits.shape[0]
+    if exact is None:
+        exact = logits_exact(hidden_bits.reshape(B * N, H), weight_bits)
+    _, bits = bf16_round(exact)
+    bits = bits.reshape(B, N, V)
+    out = mars_ref.verify(bits, draft_tokens, tree_parent, theta, temperature, uniforms, draft_probs, indicator)
+    out["logits_bits"] = bits
+    out["exact"] = exact
+    return out
+
+
 def screen_lmhead(w, clearance=4e-5, guard=1e-4, indicator=mars_ref.IND_LOGIT_RATIO, max_rounds=50, requests=None):
     """Redraw (``w.redraw_rows``) the rows of an LM-head workload whose deciding logits lie within
     ``clearance`` (relative) of a bf16 rounding boundary, or whose low-margin quantity lies within

@@ -83,6 +83,12 @@ def lib():
                                          + [ctypes.c_void_p] * 7
                                          + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                             ctypes.POINTER(VerifyOptionsStruct)])
+        L.mars_lmhead_verify_sampling.restype = ctypes.c_int
+        L.mars_lmhead_verify_sampling.argtypes = (
+            [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+             ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+             ctypes.c_void_p] + [ctypes.c_void_p] * 8
+            + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(VerifyOptionsStruct)])
         _lib = L
     return _lib
 
@@ -362,3 +368,50 @@ def mars_lmhead_verify(hidden: torch.Tensor, weight: torch.Tensor, draft_tokens:
                                     _ptr(out.stats), _ptr(workspace), workspace.numel(), _stream(),
                                     ctypes.byref(opt)))
     return out
+
+
+def mars_lmhead_verify_sampling(hidden: torch.Tensor, weight: torch.Tensor, draft_tokens: torch.Tensor,
+                                tree_parent: torch.Tensor, theta: torch.Tensor, temperature: float,
+                                uniforms: torch.Tensor, draft_probs: torch.Tensor = None,
+                                logits_out: torch.Tensor = None, out: VerifyOutputs = None,
+                                workspace: torch.Tensor = None, indicator: int = MARS_IND_LOGIT_RATIO,
+                                n_theta: int = 1, want_commit: bool = False, spin_limit: int = 0, stages: int = 0):
+    """Sampling-mode verification from the last hidden states [B,N,H] and the LM-head weight [V,H] (both bf16, or
+    their bit patterns): one kernel forms the logits, writes them to ``logits_out`` [B,N,V] (bf16 bit patterns) and
+    takes each row's top-2 and sum of exponentials on the way; the sampling walk follows.  Returns
+    (outputs, logits_out).  See include/mars.h."""
+    B, N, H = hidden.shape
+    V = weight.shape[0]
+    dev = hidden.device
+    assert hidden.is_contiguous() and weight.is_contiguous() and weight.shape == (V, H)
+    assert _dtype_code(hidden) == MARS_BF16 and _dtype_code(weight) == MARS_BF16
+    assert draft_tokens.dtype == torch.int32 and draft_tokens.shape == (B, N) and draft_tokens.is_contiguous()
+    assert tree_parent.dtype == torch.int32 and tree_parent.shape == (B, N) and tree_parent.is_contiguous()
+    assert theta.dtype == torch.float32 and theta.numel() == n_theta * B and theta.is_contiguous()
+    assert uniforms.dtype == torch.float32 and uniforms.shape == (B, N + 1) and uniforms.is_contiguous()
+    dcode = 0
+    if draft_probs is not None:
+        assert draft_probs.shape == (B, N, V) and draft_probs.is_contiguous()
+        dcode = _dtype_code(draft_probs)
+    if logits_out is None:
+        logits_out = torch.empty((B, N, V), dtype=torch.uint16, device=dev)
+    assert logits_out.shape == (B, N, V) and logits_out.is_contiguous() and _dtype_code(logits_out) == MARS_BF16
+    if out is None:
+        out = VerifyOutputs(B, N, dev, want_diag=True, n_theta=n_theta, want_commit=want_commit)
+    assert out.n_theta == n_theta
+    if workspace is None:
+        n = mars_lmhead_workspace_bytes(B, N, V, H, n_theta)
+        if n == 0:
+            raise MarsError(f"sizes out of range: B={B} N={N} V={V} H={H} n_theta={n_theta}")
+        workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+    opt = VerifyOptionsStruct(int(indicator), int(n_theta), int(spin_limit), int(stages),
+                              None if out.out_tokens is None else out.out_tokens.data_ptr(),
+                              None if out.out_len is None else out.out_len.data_ptr(),
+                              None if out.keep_rows is None else out.keep_rows.data_ptr(),
+                              None if out.keep_offsets is None else out.keep_offsets.data_ptr())
+    _check(lib().mars_lmhead_verify_sampling(
+        _ptr(hidden), _ptr(weight), H, _ptr(draft_tokens), _ptr(tree_parent), _ptr(draft_probs), dcode, _ptr(theta),
+        float(temperature), _ptr(uniforms), B, N, V, _ptr(logits_out), _ptr(out.accept_mask), _ptr(out.accept_len),
+        _ptr(out.path_idx), _ptr(out.bonus_token), _ptr(out.decision), _ptr(out.request_status), _ptr(out.stats),
+        _ptr(out.diag), _ptr(workspace), workspace.numel(), _stream(), ctypes.byref(opt)))
+    return out, logits_out

@@ -61,11 +61,16 @@ __device__ __forceinline__ void lm_load_frags(u32x4 (&f)[n], const bf16_t* first
   for (int i = 0; i < n; ++i) f[i] = *reinterpret_cast<const u32x4*>(first + i * 32 * kLmStride);
 }
 
-template <int BM>
+// SAMPLING (Eq. 2 followed by Eq. 3): the rounded logits are also written out, once, from the registers
+// they are formed in (the residual passes of the sampling walk read rows of them again), and each row's
+// sum of exp2(z*c - ref) is taken on the way, against an integer-valued reference per row that moves up with
+// the row's running maximum -- the same (reference, sum) pairs the streaming row reduction leaves.
+template <int BM, bool SAMPLING>
 __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t* __restrict__ hidden,
                                                                    const bf16_t* __restrict__ weight, int M, int V,
                                                                    int H, int slabs, int tiles_n, int tiles_per_run,
-                                                                   int runs, Partial* __restrict__ partials) {
+                                                                   int runs, Partial* __restrict__ partials,
+                                                                   bf16_t* __restrict__ logits_out, float c) {
   constexpr int WM = BM / 2;      // hidden-state rows per wave
   constexpr int IB = WM / 32;     // 32-row blocks per wave
   constexpr int JB = 4;           // 32-entry vocabulary blocks per wave (128 entries)
@@ -101,8 +106,9 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
     a_off[i] = static_cast<unsigned int>(min(M - 1 - m0, srow + i * 32)) * H + schunk;
 
   unsigned long long best1[IB], best2[IB];
+  float sref[IB], ssum[IB];  // SAMPLING: reference (already times c) and sum of this lane's share of its rows
 #pragma unroll
-  for (int ib = 0; ib < IB; ++ib) { best1[ib] = 0ull; best2[ib] = 0ull; }
+  for (int ib = 0; ib < IB; ++ib) { best1[ib] = 0ull; best2[ib] = 0ull; sref[ib] = -1.0e30f; ssum[ib] = 0.0f; }
 
   // The run is one sequence of steps (tile, slab of 64) whose operand requests do not stop at
   // tile boundaries.  A step's operands are requested kLmDepth steps ahead into one of kLmDepth
@@ -276,6 +282,42 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
         top2_insert(best1[ib], best2[ib], make_key(lm_key_value(k1), nbase + 127 - (k1 & 0x7F)));
       if (k2 != kNone)
         top2_insert(best1[ib], best2[ib], make_key(lm_key_value(k2), nbase + 127 - (k2 & 0x7F)));
+      if (SAMPLING && k1 != kNone) {
+        // Second pass over the block row, now that its maximum is known: move the reference if the maximum
+        // has risen above it (references are integers, so sums against different ones combine by exact
+        // powers of two), store the rounded logits -- four consecutive entries, 8 bytes, at a time; lane
+        // l + 32 holds the next four -- and add their exponentials.
+        const float nref = __builtin_ceilf(lm_key_value(k1) * c);
+        if (nref > sref[ib]) {
+          ssum[ib] *= __builtin_amdgcn_exp2f(sref[ib] - nref);
+          sref[ib] = nref;
+        }
+        const int row = m0 + wm * WM + ib * 32 + l32;
+        bf16_t* __restrict__ orow = logits_out + static_cast<size_t>(min(row, M - 1)) * static_cast<size_t>(V);
+        float add = 0.0f;
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) {
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const f32x2_t p0 = {acc[jb][ib][4 * q4], acc[jb][ib][4 * q4 + 1]};
+            const f32x2_t p1 = {acc[jb][ib][4 * q4 + 2], acc[jb][ib][4 * q4 + 3]};
+            const uint32_t w0 = __builtin_bit_cast(uint32_t, __builtin_convertvector(p0, bf16x2_t));
+            const uint32_t w1 = __builtin_bit_cast(uint32_t, __builtin_convertvector(p1, bf16x2_t));
+            const int e = jb * 32 + 8 * q4;  // first of the four entries, relative to nbase
+            if (!ragged || nbase + e + 3 < V) {
+              if (row < M) *reinterpret_cast<uint2*>(orow + nbase + e) = make_uint2(w0, w1);
+              const float x0 = __uint_as_float(w0 << 16), x1 = __uint_as_float(w0 & 0xFFFF0000u);
+              const float x2 = __uint_as_float(w1 << 16), x3 = __uint_as_float(w1 & 0xFFFF0000u);
+              add += (__builtin_amdgcn_exp2f(__builtin_fmaf(x0, c, -sref[ib])) +
+                      __builtin_amdgcn_exp2f(__builtin_fmaf(x1, c, -sref[ib]))) +
+                     (__builtin_amdgcn_exp2f(__builtin_fmaf(x2, c, -sref[ib])) +
+                      __builtin_amdgcn_exp2f(__builtin_fmaf(x3, c, -sref[ib])));
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        ssum[ib] += add;
+      }
     }
   }
 #undef MARS_LM_REQUEST
@@ -287,16 +329,32 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
   // (row, run).
   __syncthreads();  // every wave is done with the operand stages
   unsigned long long* xch = reinterpret_cast<unsigned long long*>(&sh_a[0][0][0]);  // [wm][ib][32 rows][2 keys]
+  float* xsum = reinterpret_cast<float*>(xch + 2 * IB * 32 * 2);                   // [wm][ib][32 rows][ref, sum]
   unsigned long long r1[IB], r2[IB];
+  float rR[IB];
+  double rS[IB];
 #pragma unroll
   for (int ib = 0; ib < IB; ++ib) {
     const unsigned long long o1 = __shfl_xor(best1[ib], 32, kWave), o2 = __shfl_xor(best2[ib], 32, kWave);
     r1[ib] = best1[ib]; r2[ib] = best2[ib];
     top2_insert(r1[ib], r2[ib], o1);
     top2_insert(r1[ib], r2[ib], o2);
+    rR[ib] = -3.0e38f; rS[ib] = 0.0;
+    if (SAMPLING) {
+      const float oR = __shfl_xor(sref[ib], 32, kWave), oS = __shfl_xor(ssum[ib], 32, kWave);
+      // (both halves add in the order lower half, upper half: the same bits in either lane)
+      const float aR = half == 0 ? sref[ib] : oR, aS = half == 0 ? ssum[ib] : oS;
+      const float bR = half == 0 ? oR : sref[ib], bS = half == 0 ? oS : ssum[ib];
+      if (aS > 0.0f) absorb_sum(rR[ib], rS[ib], aR, static_cast<double>(aS));
+      if (bS > 0.0f) absorb_sum(rR[ib], rS[ib], bR, static_cast<double>(bS));
+    }
     if (wn == 1 && half == 0) {
       xch[((wm * IB + ib) * 32 + l32) * 2 + 0] = r1[ib];
       xch[((wm * IB + ib) * 32 + l32) * 2 + 1] = r2[ib];
+      if (SAMPLING) {
+        xsum[((wm * IB + ib) * 32 + l32) * 2 + 0] = rR[ib];
+        xsum[((wm * IB + ib) * 32 + l32) * 2 + 1] = static_cast<float>(rS[ib]);
+      }
     }
   }
   __syncthreads();
@@ -311,6 +369,13 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_reduce_kernel(const bf16_t*
       out.z1 = neg_inf(); out.id1 = -1; out.z2 = neg_inf(); out.id2 = -1; out.s = 0.0f; out.ref = 0.0f;
       if (k1 != 0ull) { out.z1 = key_value(k1); out.id1 = key_index(k1); }
       if (k2 != 0ull) { out.z2 = key_value(k2); out.id2 = key_index(k2); }
+      if (SAMPLING) {
+        float R = rR[ib];
+        double S = rS[ib];
+        const float oS = xsum[((wm * IB + ib) * 32 + l32) * 2 + 1];
+        if (oS > 0.0f) absorb_sum(R, S, xsum[((wm * IB + ib) * 32 + l32) * 2 + 0], static_cast<double>(oS));
+        if (S > 0.0) { out.s = static_cast<float>(S); out.ref = R; }
+      }
       partials[static_cast<size_t>(row) * runs + run] = out;
     }
   }

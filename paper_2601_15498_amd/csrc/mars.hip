@@ -176,7 +176,8 @@ static LmPlan lm_plan(long rows, int V) {
 
 struct LmLayout {
   LmPlan plan;
-  size_t partials_off, stats_off, total;
+  int G;  // work-groups per request of the sampling walk
+  size_t partials_off, stats_off, xslots_off, total;
 };
 static LmLayout lm_layout(int B, int N, int V, int K) {
   LmLayout L;
@@ -184,7 +185,9 @@ static LmLayout lm_layout(int B, int N, int V, int K) {
   L.plan = lm_plan(rows, V);
   L.partials_off = 0;
   L.stats_off = align_up(static_cast<size_t>(rows) * L.plan.parts * sizeof(Partial));
-  L.total = L.stats_off + align_up(static_cast<size_t>(K) * rows * sizeof(mars_row_stat));
+  L.G = choose_groups(K * B, V);
+  L.xslots_off = L.stats_off + align_up(static_cast<size_t>(K) * rows * sizeof(mars_row_stat));
+  L.total = L.xslots_off + align_up(static_cast<size_t>(K) * B * (N + 2) * 2 * L.G * sizeof(unsigned long long));
   return L;
 }
 
@@ -207,6 +210,55 @@ static void* static_scratch() {
     g_scratch_ptr[dev] = p;
   }
   return g_scratch_ptr[dev];
+}
+
+// The sampling walk: G work-groups per request (a.G), a.B requests.  draft_dtype < 0: one-hot.
+static hipError_t launch_sampling_tail(const TailArgs& a, int logits_dtype, int draft_dtype, hipStream_t stream) {
+  const int V = a.V;
+  const bool dense = draft_dtype >= 0;
+  // Slices of at most kResident groups of eight per thread stay in registers between passes.
+  const int ngroups8 = (V + 7) / 8;
+  const int slice8 = ((ngroups8 + a.G - 1) / a.G + kWave - 1) / kWave * kWave;
+  const bool resident = slice8 <= kResident * kSamplingThreads;
+  const bool qbf = dense && draft_dtype == MARS_BF16;
+  const void* kernel;
+  // groups of eight elements as single aligned loads: whole rows of groups, arrays on 16-byte boundaries
+  const bool vec = (V % 8 == 0) && (reinterpret_cast<uintptr_t>(a.logits) % 16 == 0) &&
+                   (!dense || reinterpret_cast<uintptr_t>(a.dprobs) % 16 == 0);
+#define MARS_PICK2(TT, QQ, VV) (resident ? reinterpret_cast<const void*>(&tail_sampling_resident_kernel<TT, QQ, VV>) \
+                                         : reinterpret_cast<const void*>(&tail_sampling_streamed_kernel<TT, QQ, VV>))
+#define MARS_PICK(TT, QQ) (vec ? MARS_PICK2(TT, QQ, true) : MARS_PICK2(TT, QQ, false))
+  if (logits_dtype == MARS_BF16) kernel = qbf ? MARS_PICK(bf16_t, bf16_t) : MARS_PICK(bf16_t, float);
+  else kernel = qbf ? MARS_PICK(float, bf16_t) : MARS_PICK(float, float);
+#undef MARS_PICK
+#undef MARS_PICK2
+  TailArgs copy = a;
+  void* params[] = {&copy};
+  // With G > 1 the work-groups of a request exchange sums.  The grid never exceeds one work-group
+  // per compute unit, so on a GPU that is free to run it all of them are resident together and the
+  // exchanges take a couple of microseconds; when other work keeps some of them waiting for a
+  // compute unit, those that run work out the missing sums themselves (tail.h: exchange_begin) --
+  // slower, same bits, and no work-group ever depends on another one being there.
+  return hipLaunchKernel(kernel, dim3(static_cast<unsigned int>(a.B) * a.G),
+                         dim3(resident ? kSamplingThreads : kStreamingThreads), params, 0, stream);
+}
+
+// Work-groups per request at launch: what the workspace was laid out for, fewer on a GPU with fewer compute units.
+static int launch_groups(int G, int KB) {
+  if (static_cast<long>(KB) * G > compute_units()) {
+    G = compute_units() / KB;
+    if (G < 1) G = 1;
+  }
+  return G;
+}
+
+// Zeroes words (the exchange words of the sampling walk, request status words) where no row reduction
+// runs in front of the walk to do it.
+__global__ __launch_bounds__(256) void clear_words_kernel(unsigned long long* words, long nwords, int32_t* status,
+                                                          int nstatus) {
+  const long i = static_cast<long>(blockIdx.x) * 256 + threadIdx.x;
+  if (i < nwords) words[i] = 0ull;
+  if (status && i < nstatus) status[i] = 0;
 }
 
 static bool lm_sizes_ok(int B, int N, int V, int H, int K) {
@@ -358,12 +410,7 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
   a.stats = stats;
   a.stats_ws = reinterpret_cast<mars_row_stat*>(ws + L.stats_off);
   a.gathered = reinterpret_cast<const float2*>(ws + L.gathered_off);
-  int groups = L.G;
-  if (static_cast<long>(K) * B * groups > compute_units()) {
-    groups = compute_units() / (K * B);
-    if (groups < 1) groups = 1;
-  }
-  a.G = sampling ? groups : 1;
+  a.G = sampling ? launch_groups(L.G, K * B) : 1;
   // polls (about a microsecond each) a work-group gives a partner before it works out the partner's sum itself
   a.spin_limit = spin_limit > 0 ? spin_limit : kDefaultSpinLimit;
   a.xslots = clr.xslots;
@@ -386,32 +433,7 @@ int mars_verify_ex(const void* logits, int logits_dtype, const int32_t* draft_to
     hipLaunchKernelGGL(tail_greedy_kernel, dim3(static_cast<unsigned int>(K * B)), dim3(kGreedyThreads), 0, stream, a);
     return finish();
   }
-  // Slices of at most kResident groups of eight per thread stay in registers between passes.
-  const int ngroups8 = (V + 7) / 8;
-  const int slice8 = ((ngroups8 + a.G - 1) / a.G + kWave - 1) / kWave * kWave;
-  const bool resident = slice8 <= kResident * kSamplingThreads;
-  const bool qbf = dense && draft_dtype == MARS_BF16;
-  const void* kernel;
-  // groups of eight elements as single aligned loads: whole rows of groups, arrays on 16-byte boundaries
-  const bool vec = (V % 8 == 0) && (reinterpret_cast<uintptr_t>(logits) % 16 == 0) &&
-                   (!dense || reinterpret_cast<uintptr_t>(draft_probs) % 16 == 0);
-#define MARS_PICK2(TT, QQ, VV) (resident ? reinterpret_cast<const void*>(&tail_sampling_resident_kernel<TT, QQ, VV>) \
-                                         : reinterpret_cast<const void*>(&tail_sampling_streamed_kernel<TT, QQ, VV>))
-#define MARS_PICK(TT, QQ) (vec ? MARS_PICK2(TT, QQ, true) : MARS_PICK2(TT, QQ, false))
-  if (logits_dtype == MARS_BF16) kernel = qbf ? MARS_PICK(bf16_t, bf16_t) : MARS_PICK(bf16_t, float);
-  else kernel = qbf ? MARS_PICK(float, bf16_t) : MARS_PICK(float, float);
-#undef MARS_PICK
-#undef MARS_PICK2
-  void* params[] = {&a};
-  // With G > 1 the work-groups of a request exchange sums.  The grid never exceeds one work-group
-  // per compute unit, so on a GPU that is free to run it all of them are resident together and the
-  // exchanges take a couple of microseconds; when other work keeps some of them waiting for a
-  // compute unit, those that run work out the missing sums themselves (tail.h: exchange_begin) --
-  // slower, same bits, and no work-group ever depends on another one being there.
-  if (hipLaunchKernel(kernel, dim3(static_cast<unsigned int>(K * B) * a.G), dim3(resident ? kSamplingThreads : kStreamingThreads), params, 0,
-                      stream) !=
-      hipSuccess)
-    return MARS_ERR_HIP;
+  if (launch_sampling_tail(a, logits_dtype, dense ? draft_dtype : -1, stream) != hipSuccess) return MARS_ERR_HIP;
   return finish();
 }
 
@@ -514,8 +536,8 @@ int mars_lmhead_verify(const void* hidden, const void* weight, int H, const int3
   const bf16_t* hp = static_cast<const bf16_t*>(hidden);
   const bf16_t* wp = static_cast<const bf16_t*>(weight);
 #define MARS_LM_LAUNCH(BM)                                                                                      \
-  hipLaunchKernelGGL((lmhead_reduce_kernel<BM>), grid, block, 0, stream, hp, wp, rows, V, H, p.slabs, p.tiles_n, \
-                     p.tiles_per_run, p.runs, partials)
+  hipLaunchKernelGGL((lmhead_reduce_kernel<BM, false>), grid, block, 0, stream, hp, wp, rows, V, H, p.slabs, p.tiles_n, \
+                     p.tiles_per_run, p.runs, partials, static_cast<bf16_t*>(nullptr), 0.0f)
   if (lm_stages & MARS_STAGE_ROWS) {
     switch (p.bm) {
       case 64: MARS_LM_LAUNCH(64); break;
@@ -539,6 +561,97 @@ int mars_lmhead_verify(const void* hidden, const void* weight, int H, const int3
   a.ind.kind = indicator; a.ind.cind = indicator_scale(0.0f);
   a.out_tok = out_tokens; a.out_len = out_len;
   hipLaunchKernelGGL(tail_greedy_kernel, dim3(static_cast<unsigned int>(K * B)), dim3(kGreedyThreads), 0, stream, a);
+  if (hipGetLastError() != hipSuccess) return MARS_ERR_HIP;
+  if (!keep_rows) return MARS_OK;
+  hipLaunchKernelGGL(compact_keep_kernel, dim3(static_cast<unsigned int>(K)), dim3(kKeepThreads), 0, stream, out_len,
+                     path_idx, B, N, keep_rows, keep_offsets);
+  return hipGetLastError() == hipSuccess ? MARS_OK : MARS_ERR_HIP;
+}
+
+int mars_lmhead_verify_sampling(const void* hidden, const void* weight, int H, const int32_t* draft_tokens,
+                                const int32_t* tree_parent, const void* draft_probs, int draft_dtype,
+                                const float* theta, float temperature, const float* uniforms, int B, int N, int V,
+                                void* logits_out, uint8_t* accept_mask, int32_t* accept_len, int32_t* path_idx,
+                                int32_t* bonus_token, uint8_t* decision, int32_t* request_status,
+                                mars_row_stat* stats, mars_req_diag* diag, void* workspace, size_t workspace_bytes,
+                                void* hip_stream, const mars_verify_options* options) {
+  using namespace mars;
+  if (!hidden || !weight || !draft_tokens || !tree_parent || !theta || !uniforms || !logits_out || !accept_mask ||
+      !accept_len || !path_idx || !bonus_token)
+    return MARS_ERR_ARG;
+  if (reinterpret_cast<uintptr_t>(hidden) % 16 != 0 || reinterpret_cast<uintptr_t>(weight) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(logits_out) % 16 != 0 || V % 8 != 0)
+    return MARS_ERR_ARG;
+  if (!(temperature > 0.0f) || std::isinf(temperature)) return MARS_ERR_ARG;
+  const bool dense = draft_probs != nullptr;
+  if (dense && draft_dtype != MARS_F32 && draft_dtype != MARS_BF16) return MARS_ERR_DTYPE;
+  int K = 1, indicator = MARS_IND_LOGIT_RATIO, spin_limit = 0, lm_stages = MARS_STAGE_ROWS | MARS_STAGE_REQUESTS;
+  int32_t *out_tokens = nullptr, *out_len = nullptr, *keep_rows = nullptr, *keep_offsets = nullptr;
+  if (options) {
+    K = options->n_theta == 0 ? 1 : options->n_theta;
+    indicator = options->indicator;
+    spin_limit = options->spin_limit;
+    if (spin_limit < 0 || options->stages < 0 || options->stages > 3) return MARS_ERR_ARG;
+    if (options->stages != 0) lm_stages = options->stages;
+    out_tokens = options->out_tokens; out_len = options->out_len;
+    keep_rows = options->keep_rows; keep_offsets = options->keep_offsets;
+  }
+  if (indicator != MARS_IND_LOGIT_RATIO && indicator != MARS_IND_PROB_RATIO && indicator != MARS_IND_LOGIT_GAP)
+    return MARS_ERR_ARG;
+  const int given = (out_tokens != nullptr) + (out_len != nullptr) + (keep_rows != nullptr) + (keep_offsets != nullptr);
+  if (given != 0 && given != 4) return MARS_ERR_ARG;
+  if (!lm_sizes_ok(B, N, V, H, K)) return MARS_ERR_ARG;
+  const LmLayout L = lm_layout(B, N, V, K);
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0 || workspace_bytes < L.total)
+    return MARS_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int rows = B * N;
+  char* ws = static_cast<char*>(workspace);
+  Partial* partials = reinterpret_cast<Partial*>(ws + L.partials_off);
+  unsigned long long* xslots = reinterpret_cast<unsigned long long*>(ws + L.xslots_off);
+  const LmPlan& p = L.plan;
+  const float c = log2e_over_t(temperature);
+
+  if (lm_stages & MARS_STAGE_ROWS) {
+    // What the streaming row reduction clears for the walk behind it, the fused kernel does not.
+    const long nwords = static_cast<long>(K) * B * (N + 2) * 2 * L.G;
+    const long nclear = nwords > static_cast<long>(K) * B ? nwords : static_cast<long>(K) * B;
+    hipLaunchKernelGGL(clear_words_kernel, dim3(static_cast<unsigned int>((nclear + 255) / 256)), dim3(256), 0, stream,
+                       xslots, nwords, request_status, K * B);
+    const int pairs = p.runs * p.slabs, per_die = (pairs + kDies - 1) / kDies;
+    const dim3 grid(static_cast<unsigned int>(kDies * per_die)), block(kLmThreads);
+    const bf16_t* hp = static_cast<const bf16_t*>(hidden);
+    const bf16_t* wp = static_cast<const bf16_t*>(weight);
+    bf16_t* lo = static_cast<bf16_t*>(logits_out);
+#define MARS_LM_LAUNCH(BM)                                                                                            \
+  hipLaunchKernelGGL((lmhead_reduce_kernel<BM, true>), grid, block, 0, stream, hp, wp, rows, V, H, p.slabs, p.tiles_n, \
+                     p.tiles_per_run, p.runs, partials, lo, c)
+    switch (p.bm) {
+      case 64: MARS_LM_LAUNCH(64); break;
+      case 128: MARS_LM_LAUNCH(128); break;
+      default: MARS_LM_LAUNCH(192); break;
+    }
+#undef MARS_LM_LAUNCH
+    if (hipGetLastError() != hipSuccess) return MARS_ERR_HIP;
+  }
+  if (!(lm_stages & MARS_STAGE_REQUESTS)) return MARS_OK;
+
+  TailArgs a;
+  a.logits = logits_out; a.tok = draft_tokens; a.par = tree_parent;
+  a.dprobs = dense ? draft_probs : nullptr;
+  a.theta = theta; a.u = uniforms; a.partials = partials;
+  a.gathered = nullptr;  // the walk gathers for itself: no streaming row reduction has run
+  a.stats = stats;
+  a.stats_ws = reinterpret_cast<mars_row_stat*>(ws + L.stats_off);
+  a.G = launch_groups(L.G, K * B);
+  a.spin_limit = spin_limit > 0 ? spin_limit : kDefaultSpinLimit;
+  a.xslots = xslots;
+  a.mask = accept_mask; a.len = accept_len; a.path = path_idx; a.bonus = bonus_token;
+  a.dec = decision; a.status = request_status; a.diag = diag;
+  a.B = K * B; a.Bd = B; a.N = N; a.V = V; a.splits = p.parts; a.c = c;
+  a.ind.kind = indicator; a.ind.cind = indicator_scale(temperature);
+  a.out_tok = out_tokens; a.out_len = out_len;
+  if (launch_sampling_tail(a, MARS_BF16, dense ? draft_dtype : -1, stream) != hipSuccess) return MARS_ERR_HIP;
   if (hipGetLastError() != hipSuccess) return MARS_ERR_HIP;
   if (!keep_rows) return MARS_OK;
   hipLaunchKernelGGL(compact_keep_kernel, dim3(static_cast<unsigned int>(K)), dim3(kKeepThreads), 0, stream, out_len,

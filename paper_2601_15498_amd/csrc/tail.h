@@ -29,6 +29,7 @@ struct TailArgs {
   const float* u;
   const Partial* partials;
   const float2* gathered;   // sampling mode: (logit, draft probability) of every node's token in its parent's row
+                            // (left by the row reduction; nullptr: the walk gathers them itself)
   mars_row_stat* stats;     // optional caller's table [B*N]
   mars_row_stat* stats_ws;  // [B*N] in the workspace: the table the tail itself reads
   uint8_t* mask;
@@ -592,8 +593,10 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
         // (the streamed form is short of registers here: its partial results are requested further down)
         if (RESIDENT && few) load_partials_of_row(a.partials + (rd + i) * a.splits, a.splits, pq[t]);
         uv[t] = ureq[i];
-        const float2 zq = a.gathered[rd + i];
-        zx[t] = zq.x; qx[t] = zq.y;
+        if (a.gathered) {
+          const float2 zq = a.gathered[rd + i];
+          zx[t] = zq.x; qx[t] = zq.y;
+        }
       }
     }
     const float u_draw = tid == 0 ? ureq[N] : 0.0f;  // the uniform of the final draw
@@ -610,7 +613,13 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
           if (p < 0 || p >= i) bad |= 1;
           if (x < 0 || x >= V) bad |= 2;
         }
-        if (i == 0 || bad != 0) { zx[t] = 0.0f; qx[t] = 1.0f; }  // (nothing was gathered for these)
+        if (i == 0 || bad != 0) {  // (nothing was gathered for these)
+          zx[t] = 0.0f; qx[t] = 1.0f;
+        } else if (!a.gathered) {  // behind the fused LM head nobody has gathered: a second trip to memory
+          const size_t at = static_cast<size_t>(p) * V + x;
+          zx[t] = widen(zall[at]);
+          if (dense) qx[t] = widen(qall[at]);
+        }
         sh_par[i] = static_cast<int16_t>(p);
         sh_tok[i] = x;
         if (bad) atomicOr(&sh_bad, bad);

@@ -124,12 +124,13 @@ def assert_prefix_parity(w, ref, outs, b, label, k=None):
     assert 0 <= int(sel(outs["bonus_token"])) < w.V and int(sel(outs["request_status"])) == 0
 
 
-def compare(w, label=None, screened=True, cdf_guard=None, allow_small_norm=False):
+def compare(w, label=None, screened=True, cdf_guard=None, allow_small_norm=False, run=None):
     """Run both sides on workload ``w`` (uniforms are screened in place first) and assert parity.
     Returns a small summary dict.  With ``allow_small_norm`` a request that meets a residual normaliser
     below the screening floor whatever uniforms are drawn is compared up to that point
     (``assert_prefix_parity``) instead of in full; their share is bounded.  The row statistics, which do
-    not depend on uniforms, are compared for every row."""
+    not depend on uniforms, are compared for every row.  ``run(w)`` replaces the plain mars_verify call (another
+    entry point that produces the same outputs from ``w``'s inputs)."""
     label = label or w.name
     say(f"[case] {label}: B={w.B} N={w.N} V={w.V} dtype={w.dtype} T={w.temperature} "
         f"dense_q={w.draft_probs is not None}")
@@ -137,7 +138,7 @@ def compare(w, label=None, screened=True, cdf_guard=None, allow_small_norm=False
         w.logits, w.draft_tokens, w.tree_parent, w.theta, w.temperature, w.uniforms, w.draft_probs)
     assert_decisions_agree_in_both_precisions(w, ref, label)
     clean = ref.get("clean", np.ones(w.B, bool))
-    out = run_gpu(w)
+    out = run(w) if run is not None else run_gpu(w)
     if not clean.all():
         assert_few_small_norm(clean, label)
         outs_np = {key: getattr(out, key).cpu().numpy() for key in

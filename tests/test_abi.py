@@ -27,7 +27,8 @@ def declared_functions():
 
 
 def test_header_declares_the_expected_entry_points():
-    assert declared_functions() == ["mars_lmhead_verify", "mars_lmhead_workspace_bytes", "mars_margin_stats",
+    assert declared_functions() == ["mars_lmhead_verify", "mars_lmhead_verify_sampling", "mars_lmhead_workspace_bytes",
+                                    "mars_margin_stats",
                                     "mars_row_reduce", "mars_row_stats", "mars_status_string",
                                     "mars_verify", "mars_verify_ex", "mars_verify_static", "mars_version",
                                     "mars_workspace_bytes",

@@ -206,3 +206,68 @@ def test_screening_a_sub_batch_describes_those_requests():
 def test_generator_rejects_a_vocabulary_too_small_for_its_rows():
     with pytest.raises(ValueError):
         make_lmhead_workload("x", B=2, N=5, H=64, V=20, tree={"kind": "chain"})
+
+
+# ---------------------------------------------------------------- sampling mode from hidden states
+def test_hand_worked_sampling_chain():
+    # H = 2, V = 3, temperature 1/ln 2, so that exp(z/T) = 2^z.  W rows: (2,0), (1,0), (0,3).
+    #  node 0: h = (1, 0) -> z = (2, 1, 0): weights 4, 2, 1, p = (4/7, 2/7, 1/7)
+    #  node 1: h = (0, 1) -> z = (0, 0, 3): weights 1, 1, 8, p = (0.1, 0.1, 0.8)
+    # Node 1 carries token 1 (one-hot draft): accepted with probability p(1) = 2/7 = 0.2857.
+    #  u1 = 0.2: accepted; the bonus token comes from row 1: u = 0.15 falls in [0.1, 0.2) -> token 1.
+    #  u1 = 0.3: rejected; residual = p without token 1 = (4/5, 0, 1/5); u = 0.9 > 0.8 -> token 2.
+    T = np.float32(1.0 / np.log(2.0))
+    w = bits_of(np.float32([[2, 0], [1, 0], [0, 3]]))
+    h = bits_of(np.float32([[[1, 0], [0, 1]]]))
+    tok, par = np.int32([[0, 1]]), np.int32([[-1, 0]])
+    out = lmhead_ref.lmhead_verify_sampling(h, w, tok, par, 2.0, T, np.float32([[0, 0.2, 0.15]]))
+    assert np.array_equal(lmhead_ref.bf16_widen(out["logits_bits"])[0], [[2, 1, 0], [0, 0, 3]])
+    assert out["accept_len"][0] == 1 and out["bonus_token"][0] == 1
+    assert abs(out["stats"]["sum_exp"][0, 0] - 7 / 4) < 1e-6 and abs(out["stats"]["sum_exp"][0, 1] - 10 / 8) < 1e-6
+    out = lmhead_ref.lmhead_verify_sampling(h, w, tok, par, 2.0, T, np.float32([[0, 0.3, 0.9]]))
+    assert out["accept_len"][0] == 0 and out["bonus_token"][0] == 2
+    assert abs(out["diag"]["last_residual_norm"][0] - 5 / 7) < 1e-6
+    # the same logits handed to the logits oracle directly give the same walk (the composition adds nothing)
+    direct = mars_ref.verify(bits_of(np.float32([[[2, 1, 0], [0, 0, 3]]])), tok, par, 2.0, T, np.float32([[0, 0.3, 0.9]]))
+    assert direct["bonus_token"][0] == 2 and direct["accept_len"][0] == 0
+
+
+def test_lattice_workloads_have_exact_fp32_sums_in_any_order():
+    # Hidden states on a grid of 2^-5, weights on a grid of 2^-10: every product is a multiple of 2^-15, and
+    # with the magnitudes of a (row, entry) pair's products adding up to less than 512 every partial sum in
+    # any order is a multiple of 2^-15 below 2^9, i.e. an fp32 number: fp32 accumulation is exact.
+    w = make_lmhead_workload("lat", B=2, N=9, H=256, V=2048, tree={"kind": "chain"}, lattice=True, temperature=0.8,
+                             dense_q=True, seed=3)
+    h = lmhead_ref.bf16_widen(w.hidden).reshape(-1, w.H)
+    W = lmhead_ref.bf16_widen(w.weight)
+    assert np.all(h * 32 == np.rint(h * 32)) and np.abs(h).max() < 8
+    assert np.all(W * 1024 == np.rint(W * 1024)) and np.abs(W).max() < 0.25
+    assert (np.abs(h) @ np.abs(W).T).max() < 512
+    exact = lmhead_ref.logits_exact(w.hidden.reshape(-1, w.H), w.weight)
+    for order in (np.arange(w.H), np.random.default_rng(0).permutation(w.H), np.arange(w.H)[::-1]):
+        acc = np.zeros(exact.shape, np.float32)
+        for k in order:
+            acc = (acc + h[:, k:k + 1].astype(np.float32) * W[:, k].astype(np.float32)[None, :]).astype(np.float32)
+        assert np.array_equal(acc.astype(np.float64), exact)
+    # planted rows still carry a low-margin pair, and the sampling inputs are there
+    assert w.uniforms.shape == (2, 10) and w.draft_probs.shape == (2, 9, 2048)
+    assert np.allclose(w.draft_probs.sum(axis=2), 1.0, atol=1e-5)
+    out = lmhead_ref.lmhead_verify_sampling(w.hidden, w.weight, w.draft_tokens, w.tree_parent, w.theta, w.temperature,
+                                            w.uniforms, w.draft_probs)
+    assert out["stats"]["relax_ok"].sum() >= 3
+    # redrawing a row keeps it on the lattice
+    w.redraw_rows([4], 1)
+    h2 = lmhead_ref.bf16_widen(w.hidden).reshape(-1, w.H)
+    assert np.all(h2 * 32 == np.rint(h2 * 32))
+    W2 = lmhead_ref.bf16_widen(w.weight)
+    assert np.all(W2 * 1024 == np.rint(W2 * 1024))
+
+
+def test_the_bound_on_the_products_holds_at_the_full_shape():
+    # rows and columns sampled from the H = 4096 shape the benchmark runs: background pairs about 125, planted at most 30
+    spec = dict(LMHEAD_CONFIGS["small"]); spec.pop("name")
+    spec.update(H=4096, V=6000)
+    w = make_lmhead_workload("lat4096", lattice=True, temperature=1.0, seed=5, **spec)
+    h = np.abs(lmhead_ref.bf16_widen(w.hidden).reshape(-1, w.H))
+    W = np.abs(lmhead_ref.bf16_widen(w.weight))
+    assert (h @ W.T).max() < 512
