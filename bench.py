@@ -118,7 +118,7 @@ def kernel_source_digest(files=("common.h", "row_reduce.h")) -> str:
 def measured_traffic():
     """HBM bytes per launch of the row reduction from the committed rocprofv3 counter runs, or
     None when there are none or the kernel source has changed since they were taken."""
-    path = os.path.join(ROOT, "profiles", "row_reduce_cfg2_traffic.json")
+    path = os.path.join(ROOT, "profiles", "row_reduce_headline_traffic.json")
     try:
         with open(path) as fh:
             t = json.load(fh)
@@ -135,7 +135,7 @@ def measured_pass_traffic():
     k1 = measured_traffic()
     if k1 is None:
         return None
-    with open(os.path.join(ROOT, "profiles", "row_reduce_cfg2_traffic.json")) as fh:
+    with open(os.path.join(ROOT, "profiles", "row_reduce_headline_traffic.json")) as fh:
         t = json.load(fh)
     if t.get("tail_source_digest") != kernel_source_digest(("common.h", "tail.h")) or "tail_hbm_bytes_per_launch" not in t:
         return None
