@@ -216,6 +216,32 @@ __device__ __forceinline__ void load8<float>(const float* __restrict__ row, int 
   }
 }
 
+// Eight consecutive elements as they lie in memory (one aligned group): requested without being looked at,
+// so that nothing waits for them until they are widened.
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> {
+  u32x4 v;
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ row, int g) {
+    v = *reinterpret_cast<const u32x4*>(row + static_cast<size_t>(g) * 8);
+  }
+  __device__ __forceinline__ void widen_to(float (&x)[8]) const {
+    x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.x & 0xFFFF0000u);
+    x[2] = __uint_as_float(v.y << 16); x[3] = __uint_as_float(v.y & 0xFFFF0000u);
+    x[4] = __uint_as_float(v.z << 16); x[5] = __uint_as_float(v.z & 0xFFFF0000u);
+    x[6] = __uint_as_float(v.w << 16); x[7] = __uint_as_float(v.w & 0xFFFF0000u);
+  }
+};
+template <> struct Raw8<float> {
+  f32x4 lo, hi;
+  __device__ __forceinline__ void load(const float* __restrict__ row, int g) {
+    lo = *reinterpret_cast<const f32x4*>(row + static_cast<size_t>(g) * 8);
+    hi = *reinterpret_cast<const f32x4*>(row + static_cast<size_t>(g) * 8 + 4);
+  }
+  __device__ __forceinline__ void widen_to(float (&x)[8]) const {
+    x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w; x[4] = hi.x; x[5] = hi.y; x[6] = hi.z; x[7] = hi.w;
+  }
+};
+
 // The residual chain at the current node: rejection j replaced f by
 // max(0, f - q_j) * inv_norm[j] (q_j dense, or one-hot at tok[j]).
 // The first kChainRegs entries live in (wave-uniform) registers, so that the per-element
@@ -713,28 +739,52 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   // The loads of the resident slice, issued when a pass first needs it.  (Issuing them on arrival at every
   // node, in case a rejection follows, was tried: the next node's loads then have to wait for the registers
   // of the previous node's, and every accepted draft costs a trip to memory -- 86 instead of 80 us per pass.)
+  // (With whole groups the loads are kept as they come until the slice is needed -- `widen_resident` -- so that
+  // a request made ahead of time is not waited for where it is made.)
+  Raw8<T> rz[kResident];
+  Raw8<TQ> rq[kResident];
+  bool rq_loaded = false;
   auto load_resident = [&]() {
 #pragma unroll
     for (int i = 0; i < kResident; ++i) {
       const int gi = g_begin + i * NT + tid;
-      if (gi < g_end) {
+      if (VEC) {
+        if (gi < g_end) {
+          rz[i].load(rv.zrow, gi);
+          if (rv.qrow && rv.use_q) rq[i].load(rv.qrow, gi);
+        }
+      } else if (gi < g_end) {
         rv.load(gi, fc[i], qv[i]);
+      }
+    }
+    rq_loaded = rv.qrow && rv.use_q;
+    raw = true;
+    have = false;
+  };
+  auto widen_resident = [&]() {
+#pragma unroll
+    for (int i = 0; i < kResident; ++i) {
+      const int gi = g_begin + i * NT + tid;
+      if (gi < g_end) {
+        if (VEC) {
+          rz[i].widen_to(fc[i]);
+          if (rq_loaded) rq[i].widen_to(qv[i]);
+        }
       } else {  // nothing there: f = 0 and q = 0 contribute nothing
 #pragma unroll
         for (int e = 0; e < 8; ++e) { fc[i][e] = neg_inf(); qv[i][e] = 0.0f; }
       }
-      if (!dense) {
+      if (!dense || (VEC && !rq_loaded)) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) qv[i][e] = 0.0f;
       }
     }
-    raw = true;
-    have = false;
   };
   // Bring the resident slice up to date with the chain (turning the raw slice into f on first use).
   auto refresh_resident = [&]() {
     if (!have) {
       if (!raw) load_resident();
+      widen_resident();
 #pragma unroll
       for (int i = 0; i < kResident; ++i)
 #pragma unroll
@@ -766,9 +816,10 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   };
 
   for (;;) {
+    const int k1 = __builtin_amdgcn_readfirstlane(sh_first[cnode]);
+    const bool leaf = k1 >= N;
     {
-      const int k1 = __builtin_amdgcn_readfirstlane(sh_first[cnode]);
-      const int code0 = k1 < N ? __builtin_amdgcn_readfirstlane(static_cast<int>(sh_code0[k1])) : 0;
+      const int code0 = !leaf ? __builtin_amdgcn_readfirstlane(static_cast<int>(sh_code0[k1])) : 0;
       if (code0 != 0) {  // the first child is accepted: nothing else at this node matters
         if (tid == 0 && g == 0) {
           a.mask[rb + k1] = 1;
@@ -785,12 +836,17 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
     rv.zrow = zall + static_cast<size_t>(cnode) * V;
     rv.qrow = dense ? qall + static_cast<size_t>(cnode) * V : nullptr;
     rv.z1 = st.z1; rv.inv_S = 1.0f / st.sum_exp;
-    rv.use_q = dense;  // a rejection pass subtracts q
+    rv.use_q = dense && !leaf;  // a rejection pass subtracts q; nothing is rejected at a leaf
     rv.ch.n = 0;
     pending_norm = false;
     have = false;
     raw = false;
     applied = 0;
+    // The walk stops here or rejects here: at a leaf the final draw reads this row, and a node whose first
+    // child is rejected under a dense draft distribution sees a pass over it either now (further children) or in
+    // the final draw.  The row's slice is requested at once, so that its trip to memory runs beside the tests
+    // below instead of behind them.  (Only here: a node that is merely passed through never asks for its row.)
+    if (RESIDENT && (leaf || dense)) load_resident();
     // The children of cnode as bit masks over the nodes (increasing node index = increasing bit), 64
     // nodes to a word.  Every wave forms the words for itself from the parents in LDS: no wave waits for
     // another one on the way down the tree.
