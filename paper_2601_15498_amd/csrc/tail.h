@@ -745,19 +745,28 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
   Raw8<TQ> rq[kResident];
   bool rq_loaded = false;
   auto load_resident = [&]() {
+    rq_loaded = rv.qrow && rv.use_q;
+    if (VEC) {
+      // No load stands under a condition, per lane or per call: a lane past the end of its slice reads the
+      // row's last group and throws it away, and when the draft probabilities are not wanted every lane reads
+      // the first 32 bytes of the logits in their place.  With a branch between two loads the compiler can no
+      // longer count what is in flight and makes each wait for the one before (three trips to memory instead
+      // of one); with a branch around them it copies what they return into the registers of the other path
+      // right away, and waits for it there.
+      const TQ* __restrict__ qsrc = rq_loaded ? rv.qrow : reinterpret_cast<const TQ*>(zall);
 #pragma unroll
-    for (int i = 0; i < kResident; ++i) {
-      const int gi = g_begin + i * NT + tid;
-      if (VEC) {
-        if (gi < g_end) {
-          rz[i].load(rv.zrow, gi);
-          if (rv.qrow && rv.use_q) rq[i].load(rv.qrow, gi);
-        }
-      } else if (gi < g_end) {
-        rv.load(gi, fc[i], qv[i]);
+      for (int i = 0; i < kResident; ++i) {
+        const int gi = min(g_begin + i * NT + tid, ngroups - 1);
+        rz[i].load(rv.zrow, gi);
+        rq[i].load(qsrc, rq_loaded ? gi : 0);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < kResident; ++i) {
+        const int gi = g_begin + i * NT + tid;
+        if (gi < g_end) rv.load(gi, fc[i], qv[i]);
       }
     }
-    rq_loaded = rv.qrow && rv.use_q;
     raw = true;
     have = false;
   };
@@ -843,10 +852,11 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
     raw = false;
     applied = 0;
     // The walk stops here or rejects here: at a leaf the final draw reads this row, and a node whose first
-    // child is rejected under a dense draft distribution sees a pass over it either now (further children) or in
-    // the final draw.  The row's slice is requested at once, so that its trip to memory runs beside the tests
+    // child is rejected sees a pass over it either now (further children) or in the final draw, unless a later
+    // child is accepted off a closed-form normaliser (one-hot draft: the request is then wasted, nothing
+    // waits for it).  The row's slice is requested at once, so that its trip to memory runs beside the tests
     // below instead of behind them.  (Only here: a node that is merely passed through never asks for its row.)
-    if (RESIDENT && (leaf || dense)) load_resident();
+    if (RESIDENT) load_resident();
     // The children of cnode as bit masks over the nodes (increasing node index = increasing bit), 64
     // nodes to a word.  Every wave forms the words for itself from the parents in LDS: no wave waits for
     // another one on the way down the tree.
