@@ -413,9 +413,9 @@ __device__ __forceinline__ double residual_mass_slice(const RowView<T, TQ>& rv, 
   for (int base = g_begin + static_cast<int>(threadIdx.x); base < g_end; base += kPassBatch * NT) {
     float z[kPassBatch][8], q[kPassBatch][8];
 #pragma unroll
-    for (int i = 0; i < kPassBatch; ++i) {
+    for (int i = 0; i < kPassBatch; ++i) {  // (no load under a per-lane condition: see the final draw)
       const int gi = base + i * NT;
-      if (gi < g_end) rv.load(gi, z[i], q[i]);
+      rv.load(gi < g_end ? gi : g_end - 1, z[i], q[i]);
     }
 #pragma unroll
     for (int i = 0; i < kPassBatch; ++i) {
@@ -1048,9 +1048,9 @@ __device__ __forceinline__ void tail_sampling_body(const TailArgs& a) {
         for (int s0 = 0; s0 < spw; s0 += kPassBatch) {
           float z[kPassBatch][8], q[kPassBatch][8];
 #pragma unroll
-          for (int i = 0; i < kPassBatch; ++i) {
-            const int gi = group_at(s0 + i);
-            if (gi >= 0) rv.load(gi, z[i], q[i]);
+          for (int i = 0; i < kPassBatch; ++i) {  // (no load under a per-lane condition: a lane without a group
+            const int gi = group_at(s0 + i);      // reads the row's last one and ignores it, and the loads of a
+            rv.load(gi >= 0 ? gi : ngroups - 1, z[i], q[i]);  // batch go out together instead of one by one)
           }
 #pragma unroll
           for (int i = 0; i < kPassBatch; ++i) {
