@@ -34,7 +34,7 @@ single calls (``config.call_us_*``).
 Prints ONE JSON line with the whole-job rows/s, two HBM roofline objects -- ``roofline``: the
 dominant kernel (the row reduction, timed by itself with HIP events on the stream it runs on);
 ``roofline_pass``: the whole call, the bytes of the logits over the time of one call -- and the CPU
-oracle timed on the host cores of the same box.
+oracle timed on the host cores of the same machine.
 """
 import argparse
 import hashlib
