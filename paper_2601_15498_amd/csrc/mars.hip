@@ -14,8 +14,8 @@
 
 namespace mars {
 
-constexpr int kMaxTargetItems = 768;    // work-groups the row reduction aims for on a large input: the three per compute unit
-                                        // that are resident together (960 rows of 151 936: 48.4 us unsplit, 50.2 split in two)
+constexpr int kMaxTargetItems = 768;    // work-groups the row reduction aims for on a large input: three per compute unit
+                                        // (four fit; 960 rows of 151 936 run faster as 960 work-groups than as 1 920)
 constexpr int kMinTargetItems = 128;    // ... and on a small one
 constexpr int kItemElemsLog2 = 16;      // in between: about one work-group per 65 536 elements
 constexpr int kMinSplitElems = 8192;    // no split shorter than this

@@ -552,8 +552,6 @@ constexpr float kClosedFormMinNorm = 0.1f; // one-hot residual: Z = 1 - f(x) is 
 constexpr int kResident = 3;               // groups of eight elements a thread can keep in registers
 
 // RESIDENT: every slice is at most kResident groups per thread (decided by the host from G and V).
-// (At most 184 registers: a work-group of the row reduction of another call -- two waves per SIMD at 72 -- then
-// still fits on a compute unit beside a resident tail's two at 184, and calls on two streams overlap.)
 // VEC: every group of eight elements is one aligned 16-byte (or 32-byte) load -- the host checks V % 8 and
 // the alignment of the arrays.  The form that checks every element against the end of the row costs some
 // eighty comparisons and as many scalar registers before the walk starts, on the critical path of every call.
