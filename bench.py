@@ -301,6 +301,10 @@ def main() -> int:
                     help="HIP streams of the additional overlapped measurement (default: 2; 1 = none, also the default "
                          "for the single-request workloads, whose figure is a latency)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--row-scan", action="store_true",
+                    help="the row reduction alone on 768, 960, 1536 and 2304 rows of the headline shape (random "
+                         "bf16 logits), both forms: what a launch costs beyond its bytes, and the rate a further "
+                         "768 rows are read at")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for hardware-counter runs: a few launches of the row reduction on the headline "
                          "workload and of a plain device copy of the same size (the calibration kernel)")
@@ -378,6 +382,40 @@ def main() -> int:
                                 margin_counts[j], wss[j])
         else:
             M.mars_verify_ex(s["logits"], s["tok"], s["par"], s["theta"], T, s["u"], s["q"], outs[j], wss[j], n_theta=K)
+
+    if args.row_scan:
+        # A launch = a part that does not shrink with the input + bytes at the marginal rate: both come out of
+        # launches on 1x, 2x and 3x the 768 rows the chip holds three work-groups per compute unit of.
+        del sets
+        res = []
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for form, temp in (("sampling", 0.7), ("greedy", 0.0)):
+            for n in (48, 60, 96, 144):
+                torch.manual_seed(n)
+                bufs = [(torch.randn(16, n, V, device=dev) * 3).to(torch.bfloat16) for _ in range(4)]
+                w = M.alloc_workspace(16, n, V, dev)
+                for z in bufs:
+                    M.mars_row_reduce(z, temp, w)
+                torch.cuda.synchronize()
+                ts = []
+                for _ in range(5):
+                    ev0.record()
+                    for i in range(40):
+                        M.mars_row_reduce(bufs[i % 4], temp, w)
+                    ev1.record()
+                    torch.cuda.synchronize()
+                    ts.append(ev0.elapsed_time(ev1) / 40 * 1e3)
+                res.append({"form": form, "rows": 16 * n, "bytes": 16 * n * V * 2, "us_min": round(min(ts), 2),
+                            "us_median": round(sorted(ts)[2], 2)})
+                del bufs, w
+        for form in ("sampling", "greedy"):
+            r = {x["rows"]: x for x in res if x["form"] == form}
+            step_us = (r[2304]["us_min"] - r[768]["us_min"]) / 2
+            res.append({"form": form, "us_per_further_768_rows": round(step_us, 2),
+                        "marginal_GBps": round(768 * V * 2 / step_us / 1e3, 1),
+                        "us_of_a_768_row_launch_beyond_that_rate": round(r[768]["us_min"] - step_us, 2)})
+        print(json.dumps({"row_scan": res}), flush=True)
+        return 0
 
     if args.pmc_probe:
         # Counter runs serialise kernels; keep the run short.  The copy moves exactly the bytes of one
