@@ -191,3 +191,22 @@ def test_source_digest_ignores_comments_and_white_space():
     assert bench._code_only(a) != bench._code_only(c)
     assert '"// kept"' in bench._code_only(a)
     assert len(bench.kernel_source_digest()) == 16
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The pass is per request and this build measures one GPU: asked for more, bench.py says so and
+    exits before it touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_traffic_capture_belongs_to_the_kernels_as_they_are():
+    """The HBM-traffic figure of the benchmark line is a stored counter capture, valid for the kernel
+    sources it names: committed together, the two must agree (otherwise the line says traffic_stale)."""
+    import bench
+    assert bench.measured_traffic() is not None
