@@ -113,6 +113,21 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   const int nb = (nv + BV - 1) / BV;
   const int nfull = nv / BV;  // batches that need no bounds check
 
+  // The first batch is requested before anything else is done: what follows up to the stream proper
+  // (clearing memory for the kernel behind this one, the tree of the request, set-up) then runs beside
+  // the first trip to memory instead of in front of it.
+  Vec<T, EPV> bufA[U], bufB[U];
+  // Unconditional loads for a full batch; bounds-checked loads (padding with -inf) for the last one.
+  auto load_full = [&](Vec<T, EPV>(&buf)[U], int k) {
+    const T* __restrict__ bp = rowp + static_cast<size_t>(v_begin + k * BV) * EPV;  // wave-uniform
+#pragma unroll
+    for (int j = 0; j < U; ++j) buf[j].load(bp, static_cast<unsigned int>(tid + j * kRowThreads));
+    // Keep the scheduler from hoisting uses of the other buffer above these loads: that would
+    // turn the wait for the previous batch into a wait before this one is even issued.
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  if (nfull > 2) load_full(bufA, 0);
+
   // Exchange words of the tail kernel that follows on the stream (xwords per (request, exchange),
   // N + 2 exchanges per request, `copies` sets of B requests): cleared here so that the call
   // needs no separate memset.  Likewise the counters a following kernel accumulates into.
@@ -184,17 +199,6 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   __shared__ int sh_done;
   if (tid == 0) sh_done = 0;
 
-  Vec<T, EPV> bufA[U], bufB[U];
-
-  // Unconditional loads for a full batch; bounds-checked loads (padding with -inf) for the last one.
-  auto load_full = [&](Vec<T, EPV>(&buf)[U], int k) {
-    const T* __restrict__ bp = rowp + static_cast<size_t>(v_begin + k * BV) * EPV;  // wave-uniform
-#pragma unroll
-    for (int j = 0; j < U; ++j) buf[j].load(bp, static_cast<unsigned int>(tid + j * kRowThreads));
-    // Keep the scheduler from hoisting uses of the other buffer above these loads: that would
-    // turn the wait for the previous batch into a wait before this one is even issued.
-    __builtin_amdgcn_sched_barrier(0);
-  };
   auto load_tail = [&](Vec<T, EPV>(&buf)[U], int k) {
     const int base = v_begin + k * BV + tid;
 #pragma unroll
@@ -277,7 +281,6 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   // code small, which matters for the cold code every wave runs once at its end.
   int k = 0;
   if (nfull > 2) {
-    load_full(bufA, 0);
     __syncthreads();
     gather_issue();
     for (; k + 2 < nfull; k += 2) {
