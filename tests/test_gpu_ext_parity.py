@@ -369,6 +369,39 @@ def test_seeded_sweep_over_shapes_and_options(seed):
     assert ran == 6
 
 
+@pytest.mark.timeout(7200)
+def test_long_seeded_sweep_when_asked_for():
+    # The same recipe over a range of seeds given in the environment (MARS_LONG_SWEEP=first:last, six cases per
+    # seed; a thousand seeds take four minutes on the GPU).  Not part of a default run.  A case whose inputs the
+    # screening cannot bring clear of the thresholds, or too many of whose requests meet a small normaliser
+    # whatever is drawn, is counted and left out: these are properties of the inputs, and their share is bounded.
+    import os
+    span = os.environ.get("MARS_LONG_SWEEP")
+    if not span:
+        pytest.skip("set MARS_LONG_SWEEP=first:last to run it")
+    first, last = (int(x) for x in span.split(":"))
+    ran = left_out = 0
+    for seed in range(first, last):
+        rng = np.random.default_rng(1000 + seed)
+        for case in range(6):
+            w, ind, ths, tree = sweep_case(rng, seed, case)
+            try:
+                compare_ex(w, indicator=ind, thetas=tiled(ths, w.B) if ths else None,
+                           cdf_guard=5e-6 if w.V > 20000 else None, allow_small_norm=True,
+                           label=f"sweep_s{seed}_c{case}: ind={ind} K={max(1, len(ths))} tree={tree}")
+                ran += 1
+            except RuntimeError as e:
+                if "guard band not reached" not in str(e):
+                    raise
+                left_out += 1
+            except AssertionError as e:
+                if "cannot be compared in full" not in str(e):
+                    raise
+                left_out += 1
+    print(f"long sweep: {ran} cases compared, {left_out} left out")
+    assert left_out * 100 <= max(ran, 100)
+
+
 def test_margin_stats_many_cells_and_no_row_output():
     # half a million cells for the top-1 logit (the counters are cleared by the row reduction itself), and the
     # per-row table left out (rows_out = NULL)
