@@ -63,6 +63,23 @@ def test_cfg2_full_other_input_sets_of_the_benchmark(k):
     compare(make_workload(f"{name}_set{k}", seed=2 + 100 * k, **spec), label=f"cfg2_set{k}", allow_small_norm=True)
 
 
+@pytest.mark.timeout(7200)
+def test_cfg2_full_further_input_sets_when_asked_for():
+    # Further input sets of the headline shape, generated like the benchmark's (seed 2 + 100 k), for k in the
+    # range given in the environment (MARS_HEADLINE_SETS=first:last; about three seconds per set).  Not part of
+    # a default run.
+    import os
+    span = os.environ.get("MARS_HEADLINE_SETS")
+    if not span:
+        pytest.skip("set MARS_HEADLINE_SETS=first:last to run it")
+    from mars_inputs import CONFIGS
+    first, last = (int(x) for x in span.split(":"))
+    for k in range(first, last):
+        spec = dict(CONFIGS[2])
+        name = spec.pop("name")
+        compare(make_workload(f"{name}_set{k}", seed=2 + 100 * k, **spec), label=f"cfg2_set{k}", allow_small_norm=True)
+
+
 def test_cfg3_full_per_request_theta():
     s = compare(make_config(3))
     assert s["relaxed"] > 0
