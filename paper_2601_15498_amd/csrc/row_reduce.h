@@ -199,6 +199,19 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
   __shared__ int sh_done;
   if (tid == 0) sh_done = 0;
 
+  auto load_edge = [&](Vec<T, EPV>(&buf)[U], int kk) {
+    const int base = v_begin + kk * BV + tid;
+#pragma unroll
+    for (int j = 0; j < U; ++j)
+      buf[j].load(rowp, static_cast<unsigned int>(min(base + j * kRowThreads, v_end - 1)));
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto trim_edge = [&](Vec<T, EPV>(&buf)[U], int kk) {
+    const int base = v_begin + kk * BV + tid;
+#pragma unroll
+    for (int j = 0; j < U; ++j)
+      if (base + j * kRowThreads >= v_end) buf[j].fill_neg_inf();
+  };
   auto load_tail = [&](Vec<T, EPV>(&buf)[U], int k) {
     const int base = v_begin + k * BV + tid;
 #pragma unroll
@@ -289,8 +302,20 @@ __global__ __launch_bounds__(kRowThreads) void row_reduce_kernel(const T* __rest
       load_full(bufA, k + 2);
       process(bufB, k + 1);
     }
+    // bufA holds batch k; at most two batches follow it (the last full one, the ragged one).  They are
+    // requested ahead like the others -- every lane loads, one past the end of the share from the share's last
+    // vector, and what such a lane has loaded is replaced when it arrives -- so that a wave does not end its
+    // stream on one or two trips to memory with nothing else in flight.  (The requests stand under no
+    // condition: where no batch follows, the last one is asked for again and not looked at.  Under a
+    // condition, even one that is the same for the whole wave, the compiler no longer knows how many loads
+    // are in flight and waits for all of them before batch k is processed.)
+    const bool more1 = k + 1 < nb, more2 = k + 2 < nb;
+    load_edge(bufB, min(k + 1, nb - 1));
     process(bufA, k);
-    ++k;
+    load_edge(bufA, min(k + 2, nb - 1));
+    if (more1) { trim_edge(bufB, k + 1); process(bufB, k + 1); }
+    if (more2) { trim_edge(bufA, k + 2); process(bufA, k + 2); }
+    k = nb;
   } else {
     __syncthreads();
     gather_issue();
